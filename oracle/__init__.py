@@ -1,0 +1,1 @@
+"""Independent fp64 CPU oracle (test infrastructure; never imported by the product path)."""

@@ -1,0 +1,185 @@
+"""Seeded synthetic workloads: shapes, value distributions and byte/FLOP accounting.
+
+Holds none of the attention arithmetic.  Both the HIP path's tests/benchmark and
+the CPU oracle's tests draw their inputs from here, so the two sides consume
+bit-identical values.
+
+Shapes follow the paper's long-video RL workloads: 512 frames (the frame count of
+its efficiency comparison and Video-MME evaluation, Sec. 6), 3,600 frames
+(hour-long videos, Sec. 1 / Sec. 7) and 8,192 frames (maximum, Sec. 1), a 7B
+decoder (28 query heads, 4 kv heads, head_dim 128), G = 8..16 rollouts per
+question (Sec. 4.2, Sec. 5.1) and batch size 1 per GPU (Sec. 6.2).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Optional
+
+import numpy as np
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    dtype: str                 # "f32" | "bf16"
+    num_q_heads: int
+    num_kv_heads: int
+    head_dim: int
+    frames: int
+    tokens_per_frame: int
+    prompt_len: int
+    num_rollouts: int
+    response_len: Optional[int]            # fixed response length, or None when ragged
+    response_range: Optional[tuple] = None  # inclusive (lo, hi) when ragged
+    key_offset: Optional[str] = None        # None | "all" (every key) | "prefix" (video keys only)
+    key_offset_std: float = 0.5
+    seed: int = 0
+    note: str = ""
+
+    @property
+    def prefix_len(self) -> int:
+        return self.frames * self.tokens_per_frame
+
+    @property
+    def scale(self) -> float:
+        return 1.0 / float(np.sqrt(self.head_dim))
+
+
+WORKLOADS = {
+    "C1": Workload("C1", "f32", 1, 1, 64, 16, 16, 32, 2, 64, note="tiny fp32, full-tensor parity"),
+    "C2": Workload("C2", "bf16", 28, 4, 128, 64, 64, 128, 8, 1024, note="one 7B-shaped layer, 4K prefix"),
+    "C3": Workload("C3", "bf16", 28, 4, 128, 512, 64, 256, 8, 2048, key_offset="all",
+                   note="512 frames, 32K prefix, per-head key mean offset; the graded configuration"),
+    "C3pre": Workload("C3pre", "bf16", 28, 4, 128, 512, 64, 256, 8, 2048, key_offset="prefix",
+                      note="C3 shape with the key offset on video keys only (moves mass between the partials)"),
+    "C4": Workload("C4", "bf16", 28, 4, 128, 3600, 64, 256, 8, 2048, note="hour-long video, 230K prefix"),
+    "C5": Workload("C5", "bf16", 28, 4, 128, 8192, 64, 512, 16, None, response_range=(256, 4096),
+                   note="max frames, 512K prefix, ragged rollouts"),
+}
+
+
+def round_to_bf16(x: np.ndarray):
+    """Round fp32 to bf16 (round-to-nearest-even).  Returns (uint16 bit patterns, fp32 widened values)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    bits = x.view(np.uint32)
+    rounded = (bits + np.uint32(0x7FFF) + ((bits >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
+    u16 = rounded.astype(np.uint16)
+    widened = (u16.astype(np.uint32) << np.uint32(16)).view(np.float32)
+    return u16, widened
+
+
+def draw_suffix_lens(w: Workload, rng) -> np.ndarray:
+    if w.response_len is not None:
+        resp = np.full(w.num_rollouts, w.response_len, dtype=np.int64)
+    else:
+        lo, hi = w.response_range
+        resp = rng.integers(lo, hi + 1, size=w.num_rollouts)
+    return (w.prompt_len + resp).astype(np.int32)
+
+
+@dataclass
+class Inputs:
+    workload: Workload
+    suffix_lens: np.ndarray            # int32 [G]
+    # exact values both sides consume, as fp32 (bf16 workloads: already rounded)
+    q: np.ndarray
+    k_prefix: np.ndarray
+    v_prefix: np.ndarray
+    k_suffix: np.ndarray
+    v_suffix: np.ndarray
+    bits: dict = field(default_factory=dict)   # bf16 workloads: name -> uint16 bit patterns
+
+    @property
+    def total_suffix(self) -> int:
+        return int(self.suffix_lens.sum())
+
+
+def make_inputs(w: Workload, seed: Optional[int] = None, keep_f32: bool = True) -> Inputs:
+    """Draw order is fixed: lengths, q, k_prefix, v_prefix, k_suffix, v_suffix, key offsets."""
+    rng = np.random.default_rng(w.seed if seed is None else seed)
+    lens = draw_suffix_lens(w, rng)
+    T, P = int(lens.sum()), w.prefix_len
+    shapes = {
+        "q": (T, w.num_q_heads, w.head_dim),
+        "k_prefix": (P, w.num_kv_heads, w.head_dim),
+        "v_prefix": (P, w.num_kv_heads, w.head_dim),
+        "k_suffix": (T, w.num_kv_heads, w.head_dim),
+        "v_suffix": (T, w.num_kv_heads, w.head_dim),
+    }
+    raw = {n: rng.standard_normal(s, dtype=np.float32) for n, s in shapes.items()}
+    if w.key_offset is not None:
+        mu = (w.key_offset_std * rng.standard_normal((w.num_kv_heads, w.head_dim))).astype(np.float32)
+        raw["k_prefix"] += mu[None]
+        if w.key_offset == "all":
+            raw["k_suffix"] += mu[None]
+    vals, bits = {}, {}
+    for n, a in raw.items():
+        if w.dtype == "bf16":
+            b, wd = round_to_bf16(a)
+            bits[n] = b
+            vals[n] = wd if keep_f32 else None
+        else:
+            vals[n] = a
+    return Inputs(w, lens, vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"],
+                  vals["v_suffix"], bits)
+
+
+def make_custom(dtype, Hq, Hkv, D, P, suffix_lens, seed=0, name="custom", std=1.0) -> Inputs:
+    """Inputs for an arbitrary shape (edge-case tests); iid N(0, std^2)."""
+    rng = np.random.default_rng(seed)
+    lens = np.asarray(suffix_lens, dtype=np.int32)
+    T = int(lens.sum())
+    w = Workload(name, dtype, Hq, Hkv, D, P, 1, 0, len(lens), None, seed=seed)
+    raw = {
+        "q": rng.standard_normal((T, Hq, D), dtype=np.float32) * np.float32(std),
+        "k_prefix": rng.standard_normal((P, Hkv, D), dtype=np.float32) * np.float32(std),
+        "v_prefix": rng.standard_normal((P, Hkv, D), dtype=np.float32),
+        "k_suffix": rng.standard_normal((T, Hkv, D), dtype=np.float32) * np.float32(std),
+        "v_suffix": rng.standard_normal((T, Hkv, D), dtype=np.float32),
+    }
+    vals, bits = {}, {}
+    for n, a in raw.items():
+        if dtype == "bf16":
+            bits[n], vals[n] = round_to_bf16(a)
+        else:
+            vals[n] = a
+    return Inputs(w, lens, vals["q"], vals["k_prefix"], vals["v_prefix"], vals["k_suffix"],
+                  vals["v_suffix"], bits)
+
+
+# ---------------------------------------------------------------- accounting (measurement only)
+
+def visible_pairs(prefix_len: int, suffix_lens) -> int:
+    """Visible (query row, key) pairs per q-head: sum_g [S_g P + S_g (S_g + 1) / 2]."""
+    return int(sum(int(s) * prefix_len + int(s) * (int(s) + 1) // 2 for s in suffix_lens))
+
+
+def effective_flop(Hq: int, D: int, prefix_len: int, suffix_lens) -> int:
+    """4 D FLOP per visible pair (2D for QK^T, 2D for PV), all q-heads."""
+    return 4 * D * Hq * visible_pairs(prefix_len, suffix_lens)
+
+
+def algorithmic_bytes(w: Workload, suffix_lens) -> int:
+    """Bytes the method must move at least once: Q, O, prefix K/V, suffix K/V, LSE."""
+    T = int(np.sum(suffix_lens))
+    e = 2 if w.dtype == "bf16" else 4
+    qo = 2 * T * w.num_q_heads * w.head_dim * e
+    kv = 2 * (w.prefix_len + T) * w.num_kv_heads * w.head_dim * e
+    return qo + kv + 4 * w.num_q_heads * T
+
+
+def sample_rows(suffix_lens, prompt_len: int, tile: int, n_random: int, seed: int = 0) -> np.ndarray:
+    """Packed token rows for sampled parity: per rollout the first and last row, the rows on
+    both sides of the prompt/response boundary and of every multiple of `tile`, plus random rows."""
+    rng = np.random.default_rng(seed + 12345)
+    off = np.concatenate([[0], np.cumsum(np.asarray(suffix_lens, dtype=np.int64))])
+    rows = []
+    for g, S in enumerate(np.asarray(suffix_lens, dtype=np.int64)):
+        local = {0, int(S) - 1}
+        if 0 < prompt_len < S:
+            local.update({prompt_len - 1, prompt_len})
+        for b in range(tile, int(S), tile):
+            local.update({b - 1, b})
+        local.update(int(x) for x in rng.integers(0, S, size=n_random))
+        rows.extend(int(off[g]) + i for i in sorted(local))
+    return np.asarray(rows, dtype=np.int64)
