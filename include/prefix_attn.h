@@ -1,0 +1,129 @@
+/* prefix_attn.h -- C ABI of the prefix-shared GRPO prefill attention library (gfx950 / MI355X).
+ *
+ * The operation (paper Sec. 4.2: G responses are sampled for one question; Sec. 5.1:
+ * the gathered video embeddings are computed once and reused by every rollout;
+ * Sec. 5.2: every rollout is prefilled over the whole multimodal sequence):
+ *
+ *   One call handles one (video, question) pair.  The video tokens form a prefix of
+ *   P tokens whose keys/values are shared by all G rollouts.  Rollout g owns a
+ *   suffix of S_g = prompt + response_g tokens.  For rollout g, query head h
+ *   (kv head c = h / (Hq/Hkv)) and suffix row i, the visible keys are all P prefix
+ *   keys of kv head c and the rollout's own suffix keys 0..i (diagonal included):
+ *
+ *       s_j = softmax_scale * <q, k_j>,   LSE = ln sum_j exp(s_j),
+ *       out = sum_j exp(s_j - LSE) v_j.
+ *
+ *   The library computes this as three kernels: a prefix pass (no mask; all rollouts'
+ *   rows of one kv head stacked against LDS-staged prefix K/V tiles), a causal suffix
+ *   pass, and a log-sum-exp merge of the two partial results.
+ *
+ * Conventions
+ *   - No C++ types, no exceptions and no printing cross this boundary.  Every call
+ *     returns a pa_status_t (0 = PA_OK); nothing aborts.
+ *   - Layouts are token-major and contiguous.  T = sum_g S_g; rollouts are packed
+ *     back to back in rollout order.
+ *   - Pointers named q, k_*, v_*, out, workspace, lse_out are DEVICE pointers on the
+ *     plan's device and must be 16-byte aligned (else PA_ERR_ALIGN).  `desc`,
+ *     `suffix_lens`, `plan_out`, `workspace_bytes_out` are HOST pointers.
+ *   - The caller owns every device buffer, including the workspace.  The plan owns
+ *     host metadata and small device-side schedule tables which prefix_attn_plan
+ *     allocates and prefix_attn_destroy frees.  prefix_attn_forward and
+ *     prefix_attn_lse allocate nothing and never synchronise: they only enqueue work
+ *     on the given stream.
+ *   - A plan is immutable; forward calls on different streams are safe when they use
+ *     different workspaces.
+ */
+#ifndef PREFIX_ATTN_H_
+#define PREFIX_ATTN_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct prefix_attn_plan prefix_attn_plan_t; /* opaque, library-owned */
+
+typedef enum {
+  PA_OK = 0,
+  PA_ERR_NULL = 1,        /* a required pointer is NULL */
+  PA_ERR_SHAPE = 2,       /* a size is out of range or inconsistent */
+  PA_ERR_UNSUPPORTED = 3, /* valid but not implemented (head_dim, dtype) */
+  PA_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
+  PA_ERR_WORKSPACE = 5,   /* workspace_bytes is smaller than the plan requires */
+  PA_ERR_ALLOC = 6,       /* host or device allocation failed in prefix_attn_plan */
+  PA_ERR_HIP = 7          /* a HIP runtime call or kernel launch failed */
+} pa_status_t;
+
+typedef enum { PA_F32 = 0, PA_BF16 = 1 } pa_dtype_t;
+
+typedef struct {
+  int32_t num_q_heads;        /* Hq >= 1 */
+  int32_t num_kv_heads;       /* Hkv >= 1, Hq % Hkv == 0; q head h reads kv head h / (Hq/Hkv) */
+  int32_t head_dim;           /* D in {64, 128} */
+  int64_t prefix_len;         /* P >= 0; 0 gives plain packed causal attention */
+  int32_t num_rollouts;       /* G >= 1 */
+  const int32_t* suffix_lens; /* HOST array [G]; S_g >= 1; copied by prefix_attn_plan */
+  float softmax_scale;        /* finite and > 0, e.g. 1/sqrt(D) */
+  int32_t dtype;              /* pa_dtype_t of q, k, v, out; LSE is always fp32 */
+  int32_t device;             /* HIP device ordinal; -1 = host-only plan (validation and
+                                 schedule only; forward/lse on it return PA_ERR_UNSUPPORTED) */
+} prefix_attn_desc_t;
+
+/* Validate `desc`, build the work lists of the prefix pass and the suffix pass and
+ * report the workspace size a forward call needs.  On success *plan_out receives a
+ * plan to be released with prefix_attn_destroy; on failure *plan_out is NULL. */
+int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_out,
+                     size_t* workspace_bytes_out);
+
+/* Enqueue prefix pass, suffix pass and merge on `hip_stream` (a hipStream_t; NULL =
+ * the default stream).
+ *   q         [T, Hq,  D]  queries of all suffix tokens
+ *   k_prefix  [P, Hkv, D]  shared video keys    (may be NULL when P == 0)
+ *   v_prefix  [P, Hkv, D]  shared video values  (may be NULL when P == 0)
+ *   k_suffix  [T, Hkv, D]  per-rollout prompt+response keys
+ *   v_suffix  [T, Hkv, D]  per-rollout prompt+response values
+ *   out       [T, Hq,  D]  attention output, same dtype as q
+ *   workspace              scratch of at least the planned size; holds the two fp32
+ *                          partial results and the merged LSE after the call
+ * Argument errors are reported before anything is launched. */
+int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                        const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
+                        void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Copy the merged log-sum-exp (natural log, fp32) of the last forward call that used
+ * `workspace` into lse_out [Hq, T].  Must be enqueued after that forward call on the
+ * same stream (or otherwise ordered after it); calling it on a workspace that no
+ * forward call has filled yields unspecified values.  LSE is the hand-off for
+ * merging with attention over further key shards. */
+int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out,
+                    void* hip_stream);
+
+/* Release a plan (NULL is allowed).  Work enqueued with the plan must have finished. */
+void prefix_attn_destroy(prefix_attn_plan_t* plan);
+
+/* Static, NUL-terminated description of a status code. */
+const char* prefix_attn_status_string(int status);
+
+/* ---- introspection of the schedule (host only; used by tests and the benchmark) ---- */
+
+/* Tile geometry: stacked query rows per work item and keys per LDS tile.  A stacked
+ * row index inside rollout g is m = i * (Hq/Hkv) + (h % (Hq/Hkv)). */
+int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_item, int32_t* keys_per_tile);
+
+/* Number of work items of a pass (0 = prefix pass, 1 = suffix pass), padding items included. */
+int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass);
+
+/* Copy the work list of a pass into items_out [num_items][4] (HOST) in launch order:
+ * {rollout g (-1 = padding item), first stacked row inside the rollout, kv head c,
+ *  number of keys the item sweeps}. */
+int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
+
+/* Total suffix tokens T of the plan. */
+int64_t prefix_attn_plan_total_tokens(const prefix_attn_plan_t* plan);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PREFIX_ATTN_H_ */

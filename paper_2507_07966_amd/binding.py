@@ -1,0 +1,189 @@
+"""Thin ctypes binding over libprefix_attn.so (the C ABI in include/prefix_attn.h).
+
+Argument marshalling only: every step of the attention runs in the library's HIP
+kernels.  PyTorch tensors are used as device memory; the binding passes raw
+device pointers and the current HIP stream.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(HERE, "libprefix_attn.so")
+_lib = None
+
+PA_F32, PA_BF16 = 0, 1
+STATUS_NAMES = {0: "PA_OK", 1: "PA_ERR_NULL", 2: "PA_ERR_SHAPE", 3: "PA_ERR_UNSUPPORTED", 4: "PA_ERR_ALIGN",
+                5: "PA_ERR_WORKSPACE", 6: "PA_ERR_ALLOC", 7: "PA_ERR_HIP"}
+EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_lse", "prefix_attn_destroy",
+                    "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
+                    "prefix_attn_plan_items", "prefix_attn_plan_total_tokens")
+
+
+class PrefixAttnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = load_library().prefix_attn_status_string(status).decode()
+        super().__init__(f"{where}: {STATUS_NAMES.get(status, status)} ({msg})")
+
+
+class _Desc(ctypes.Structure):
+    _fields_ = [("num_q_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("prefix_len", ctypes.c_int64), ("num_rollouts", ctypes.c_int32),
+                ("suffix_lens", ctypes.POINTER(ctypes.c_int32)), ("softmax_scale", ctypes.c_float),
+                ("dtype", ctypes.c_int32), ("device", ctypes.c_int32)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the C-ABI library; raises if it has not been built (python -m paper_2507_07966_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(f"{_LIB_PATH} is missing: build it with `python -m paper_2507_07966_amd.build`")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, sz = ctypes.c_void_p, ctypes.c_size_t
+    lib.prefix_attn_plan.restype = ctypes.c_int
+    lib.prefix_attn_plan.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp), ctypes.POINTER(sz)]
+    lib.prefix_attn_forward.restype = ctypes.c_int
+    lib.prefix_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prefix_attn_lse.restype = ctypes.c_int
+    lib.prefix_attn_lse.argtypes = [vp, vp, vp, vp]
+    lib.prefix_attn_destroy.restype = None
+    lib.prefix_attn_destroy.argtypes = [vp]
+    lib.prefix_attn_status_string.restype = ctypes.c_char_p
+    lib.prefix_attn_status_string.argtypes = [ctypes.c_int]
+    lib.prefix_attn_plan_tiles.restype = ctypes.c_int
+    lib.prefix_attn_plan_tiles.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int32)]
+    lib.prefix_attn_plan_num_items.restype = ctypes.c_int64
+    lib.prefix_attn_plan_num_items.argtypes = [vp, ctypes.c_int32]
+    lib.prefix_attn_plan_items.restype = ctypes.c_int
+    lib.prefix_attn_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    lib.prefix_attn_plan_total_tokens.restype = ctypes.c_int64
+    lib.prefix_attn_plan_total_tokens.argtypes = [vp]
+    _lib = lib
+    return lib
+
+
+def prefix_attn_status_string(status: int) -> str:
+    return load_library().prefix_attn_status_string(int(status)).decode()
+
+
+class PrefixAttnPlan:
+    """Owner of a prefix_attn_plan_t*; see prefix_attn_plan()."""
+
+    def __init__(self, handle, workspace_bytes, desc_kw):
+        self._h = handle
+        self.workspace_bytes = int(workspace_bytes)
+        self.__dict__.update(desc_kw)
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("plan was destroyed")
+        return self._h
+
+    @property
+    def total_tokens(self) -> int:
+        return int(load_library().prefix_attn_plan_total_tokens(self.handle))
+
+    def tiles(self):
+        a, b = ctypes.c_int32(), ctypes.c_int32()
+        st = load_library().prefix_attn_plan_tiles(self.handle, ctypes.byref(a), ctypes.byref(b))
+        if st:
+            raise PrefixAttnError(st, "prefix_attn_plan_tiles")
+        return a.value, b.value
+
+    def items(self, which: int) -> np.ndarray:
+        """Work list of pass 0 (prefix) or 1 (suffix): int32 [n, 4] = (g, row0, c, nkeys)."""
+        lib = load_library()
+        n = lib.prefix_attn_plan_num_items(self.handle, which)
+        if n < 0:
+            raise PrefixAttnError(2, "prefix_attn_plan_num_items")
+        out = np.zeros((n, 4), dtype=np.int32)
+        if n:
+            st = lib.prefix_attn_plan_items(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+            if st:
+                raise PrefixAttnError(st, "prefix_attn_plan_items")
+        return out
+
+    def destroy(self):
+        if self._h is not None:
+            load_library().prefix_attn_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def prefix_attn_plan(num_q_heads: int, num_kv_heads: int, head_dim: int, prefix_len: int,
+                     suffix_lens: Sequence[int], softmax_scale: float, dtype: str = "bf16",
+                     device: int = 0) -> PrefixAttnPlan:
+    """prefix_attn_plan of the C ABI.  dtype "bf16" | "f32"; device -1 = host-only plan."""
+    lib = load_library()
+    lens = np.ascontiguousarray(suffix_lens, dtype=np.int32)
+    d = _Desc()
+    d.num_q_heads, d.num_kv_heads, d.head_dim = int(num_q_heads), int(num_kv_heads), int(head_dim)
+    d.prefix_len, d.num_rollouts = int(prefix_len), int(len(lens))
+    d.suffix_lens = lens.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if len(lens) else None
+    d.softmax_scale = float(softmax_scale)
+    d.dtype = {"f32": PA_F32, "bf16": PA_BF16}.get(dtype, dtype if isinstance(dtype, int) else -1)
+    d.device = int(device)
+    h, ws = ctypes.c_void_p(), ctypes.c_size_t()
+    st = lib.prefix_attn_plan(ctypes.byref(d), ctypes.byref(h), ctypes.byref(ws))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_plan")
+    kw = dict(num_q_heads=d.num_q_heads, num_kv_heads=d.num_kv_heads, head_dim=d.head_dim, prefix_len=d.prefix_len,
+              suffix_lens=lens.copy(), softmax_scale=d.softmax_scale, dtype=dtype, device=d.device)
+    return PrefixAttnPlan(h, ws.value, kw)
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return int(t.data_ptr())
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if isinstance(stream, int):
+        return stream or None
+    return int(stream.cuda_stream) or None
+
+
+def prefix_attn_forward(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace,
+                        stream=None) -> None:
+    """prefix_attn_forward of the C ABI.  Tensors are torch device tensors (or raw int pointers);
+    `workspace` is a uint8 tensor of at least plan.workspace_bytes.  Enqueues only."""
+    ws_bytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else plan.workspace_bytes
+    st = load_library().prefix_attn_forward(plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix),
+                                            _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_forward")
+
+
+def prefix_attn_lse(plan: PrefixAttnPlan, workspace, lse_out, stream=None) -> None:
+    """prefix_attn_lse of the C ABI: merged LSE [Hq, T] fp32 of the last forward on `workspace`."""
+    st = load_library().prefix_attn_lse(plan.handle, _ptr(workspace), _ptr(lse_out), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_lse")
+
+
+def prefix_attn_destroy(plan: PrefixAttnPlan) -> None:
+    plan.destroy()

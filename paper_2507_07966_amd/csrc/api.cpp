@@ -1,0 +1,91 @@
+// prefix_attn_forward / prefix_attn_lse: argument checks on the host, then three launches
+// (prefix pass, suffix pass, merge) on the caller's stream.  Nothing here allocates or
+// synchronises.
+#include <hip/hip_runtime_api.h>
+
+#include "common.h"
+
+namespace {
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+}  // namespace
+
+extern "C" {
+
+int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
+                        const void* k_suffix, const void* v_suffix, void* out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  if (!plan || !q || !k_suffix || !v_suffix || !out || !workspace) return PA_ERR_NULL;
+  const prefix_attn_desc_t& d = plan->desc;
+  const bool has_prefix = d.prefix_len > 0;
+  if (has_prefix && (!k_prefix || !v_prefix)) return PA_ERR_NULL;
+  if (misaligned(q) || misaligned(k_suffix) || misaligned(v_suffix) || misaligned(out) || misaligned(workspace))
+    return PA_ERR_ALIGN;
+  if (has_prefix && (misaligned(k_prefix) || misaligned(v_prefix))) return PA_ERR_ALIGN;
+  if (workspace_bytes < plan->ws_bytes) return PA_ERR_WORKSPACE;
+  if (d.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess || cur != d.device) return PA_ERR_HIP;  // the plan's device must be current
+
+  char* ws = static_cast<char*>(workspace);
+  float* o1 = reinterpret_cast<float*>(ws + plan->off_o1);
+  float* o2 = reinterpret_cast<float*>(ws + plan->off_o2);
+  float* lse1 = reinterpret_cast<float*>(ws + plan->off_lse1);
+  float* lse2 = reinterpret_cast<float*>(ws + plan->off_lse2);
+  float* lse = reinterpret_cast<float*>(ws + plan->off_lse);
+
+  pa::PassArgs a{};
+  a.q = q;
+  a.cu = plan->d_cu;
+  a.Hq = d.num_q_heads;
+  a.Hkv = d.num_kv_heads;
+  a.D = d.head_dim;
+  a.group = plan->group;
+  a.scale = d.softmax_scale;
+  auto launch_pass = (d.dtype == PA_BF16) ? pa::launch_pass_bf16 : pa::launch_pass_f32;
+
+  if (has_prefix) {
+    a.k = k_prefix;
+    a.v = v_prefix;
+    a.o_part = o1;
+    a.lse_part = lse1;
+    a.items = plan->d_items[0];
+    a.num_items = (int64_t)plan->items[0].size();
+    a.causal = false;
+    if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
+  }
+  a.k = k_suffix;
+  a.v = v_suffix;
+  a.o_part = o2;
+  a.lse_part = lse2;
+  a.items = plan->d_items[1];
+  a.num_items = (int64_t)plan->items[1].size();
+  a.causal = true;
+  if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
+
+  pa::MergeArgs m{};
+  m.o1 = o1;
+  m.lse1 = lse1;
+  m.o2 = o2;
+  m.lse2 = lse2;
+  m.out = out;
+  m.lse = lse;
+  m.rows = plan->T * d.num_q_heads;
+  m.D = d.head_dim;
+  m.dtype = d.dtype;
+  m.has_prefix = has_prefix;
+  if (pa::launch_merge(m, hip_stream) != 0) return PA_ERR_HIP;
+  return PA_OK;
+}
+
+int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out, void* hip_stream) {
+  if (!plan || !workspace || !lse_out) return PA_ERR_NULL;
+  if (misaligned(workspace) || misaligned(lse_out)) return PA_ERR_ALIGN;
+  if (plan->desc.device < 0) return PA_ERR_UNSUPPORTED;
+  const float* lse = reinterpret_cast<const float*>(static_cast<const char*>(workspace) + plan->off_lse);
+  if (pa::launch_lse_export(lse, lse_out, plan->T, plan->desc.num_q_heads, hip_stream) != 0) return PA_ERR_HIP;
+  return PA_OK;
+}
+
+}  // extern "C"

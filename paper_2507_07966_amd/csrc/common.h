@@ -1,0 +1,75 @@
+// Internal declarations shared by the host side (plan, API) and the kernel launchers.
+// Nothing here is part of the public C ABI (see include/prefix_attn.h).
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "prefix_attn.h"
+
+namespace pa {
+
+// Tile geometry of the two attention passes: one work item = ROWS_PER_ITEM stacked query
+// rows of one (kv head, rollout); keys are swept in LDS tiles of KEYS_PER_TILE.
+constexpr int ROWS_PER_ITEM = 256;
+constexpr int KEYS_PER_TILE = 64;
+constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
+
+// One entry of a pass's work list.  g < 0 marks a padding entry (the workgroup exits).
+struct WorkItem {
+  int32_t g;      // rollout
+  int32_t row0;   // first stacked row inside the rollout, m = i * group + (h % group)
+  int32_t c;      // kv head
+  int32_t nkeys;  // keys swept: P in the prefix pass, causal extent in the suffix pass
+};
+
+// Arguments of one attention pass (prefix or suffix).  All pointers are device pointers.
+struct PassArgs {
+  const void* q;        // [T, Hq, D]
+  const void* k;        // prefix: [P, Hkv, D]; suffix: [T, Hkv, D]
+  const void* v;
+  float* o_part;        // [T, Hq, D] fp32, normalised partial output
+  float* lse_part;      // [T, Hq]    fp32, natural-log LSE of the partial
+  const WorkItem* items;
+  const int32_t* cu;    // [G+1] packed-row offsets of the rollouts
+  int64_t num_items;
+  int32_t Hq, Hkv, D, group;
+  float scale;          // softmax scale
+  bool causal;          // false: prefix pass (k/v indexed from 0, no mask); true: suffix pass
+};
+
+struct MergeArgs {
+  const float* o1;      // prefix partial (ignored when !has_prefix)
+  const float* lse1;
+  const float* o2;      // suffix partial
+  const float* lse2;
+  void* out;            // [T, Hq, D] in the plan's dtype
+  float* lse;           // [T, Hq] merged
+  int64_t rows;         // T * Hq
+  int32_t D;
+  int32_t dtype;
+  bool has_prefix;
+};
+
+// Launchers; each returns a hipError_t value as int (0 = success).  `stream` is a hipStream_t.
+int launch_pass_bf16(const PassArgs& a, void* stream);
+int launch_pass_f32(const PassArgs& a, void* stream);
+int launch_merge(const MergeArgs& a, void* stream);
+int launch_lse_export(const float* lse_th, float* lse_ht, int64_t T, int32_t Hq, void* stream);
+
+}  // namespace pa
+
+struct prefix_attn_plan {
+  prefix_attn_desc_t desc;             // suffix_lens points into `lens`
+  std::vector<int32_t> lens;           // [G]
+  std::vector<int32_t> cu;             // [G+1]
+  int64_t T = 0;
+  int32_t group = 1;                   // Hq / Hkv
+  std::vector<pa::WorkItem> items[2];  // 0 = prefix pass, 1 = suffix pass
+  // device-side copies (null for a host-only plan)
+  int32_t* d_cu = nullptr;
+  pa::WorkItem* d_items[2] = {nullptr, nullptr};
+  // workspace layout, byte offsets
+  size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, ws_bytes = 0;
+};

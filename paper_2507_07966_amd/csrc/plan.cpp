@@ -1,0 +1,198 @@
+// Host side of the library: descriptor validation, the work lists of the two attention
+// passes, workspace layout, plan lifetime and schedule introspection.
+//
+// Shapes follow the paper's rollout-and-prefill description (Sec. 4.2: G responses per
+// question; Sec. 5.1: one cached video embedding shared by all rollouts; Sec. 5.2: prefill
+// of every rollout): a shared prefix of P tokens and G ragged suffixes packed back to back.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <new>
+
+#include "common.h"
+
+using pa::WorkItem;
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+int validate(const prefix_attn_desc_t* d) {
+  if (d->num_q_heads < 1 || d->num_kv_heads < 1 || d->num_q_heads % d->num_kv_heads != 0) return PA_ERR_SHAPE;
+  if (d->head_dim < 1 || d->prefix_len < 0 || d->num_rollouts < 1) return PA_ERR_SHAPE;
+  if (!(d->softmax_scale > 0.0f) || !std::isfinite(d->softmax_scale)) return PA_ERR_SHAPE;
+  if (d->device < -1) return PA_ERR_SHAPE;
+  if (d->prefix_len > (int64_t)1 << 30) return PA_ERR_SHAPE;  // key indices are 32-bit in the kernels
+  if (!d->suffix_lens) return PA_ERR_NULL;
+  int64_t T = 0;
+  for (int g = 0; g < d->num_rollouts; ++g) {
+    if (d->suffix_lens[g] < 1) return PA_ERR_SHAPE;
+    T += d->suffix_lens[g];
+  }
+  const int64_t group = d->num_q_heads / d->num_kv_heads;
+  // stacked row indices (S_g * group) and packed rows times heads must fit 32-bit arithmetic
+  for (int g = 0; g < d->num_rollouts; ++g)
+    if ((int64_t)d->suffix_lens[g] * group > (int64_t)1 << 30) return PA_ERR_SHAPE;
+  if (T * d->num_q_heads > (int64_t)1 << 31) return PA_ERR_SHAPE;
+  if (d->dtype != PA_F32 && d->dtype != PA_BF16) return PA_ERR_UNSUPPORTED;
+  if (d->head_dim != 64 && d->head_dim != 128) return PA_ERR_UNSUPPORTED;
+  return PA_OK;
+}
+
+// Prefix pass: every (kv head, rollout, block of stacked rows) sweeps all P keys.  Workgroup n
+// runs on XCD n % 8 and each XCD has a private L2, so the list is interleaved such that one kv
+// head's items land on a fixed subset of XCDs and walk the prefix K/V tiles together: the
+// tiles are then fetched from HBM about once per XCD subset instead of once per workgroup.
+void build_prefix_items(prefix_attn_plan_t& p) {
+  std::vector<WorkItem>& out = p.items[0];
+  out.clear();
+  const int Hkv = p.desc.num_kv_heads;
+  const int P = (int)p.desc.prefix_len;
+  if (P == 0) return;
+  std::vector<std::vector<WorkItem>> per_head(Hkv);
+  for (int c = 0; c < Hkv; ++c)
+    for (int g = 0; g < p.desc.num_rollouts; ++g) {
+      const int nrows = p.lens[g] * p.group;
+      for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM) per_head[c].push_back({g, row0, c, P});
+    }
+  const size_t per = per_head[0].size();
+  if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
+    const int xper = pa::NUM_XCD / Hkv;  // XCDs per kv head
+    const size_t qlen = (per + xper - 1) / xper;
+    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0});
+    for (int x = 0; x < pa::NUM_XCD; ++x) {
+      const int c = x / xper, sub = x % xper;
+      for (size_t k = 0; k * xper + sub < per; ++k) out[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
+    }
+  } else {
+    for (int c = 0; c < Hkv; ++c) out.insert(out.end(), per_head[c].begin(), per_head[c].end());
+  }
+}
+
+// Suffix pass: a block of stacked rows needs the rollout's keys 0..(position of its last row).
+// Items are issued longest first so the ragged, triangular work packs well.
+void build_suffix_items(prefix_attn_plan_t& p) {
+  std::vector<WorkItem>& out = p.items[1];
+  out.clear();
+  for (int c = 0; c < p.desc.num_kv_heads; ++c)
+    for (int g = 0; g < p.desc.num_rollouts; ++g) {
+      const int nrows = p.lens[g] * p.group;
+      for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM) {
+        const int last_row = std::min(row0 + pa::ROWS_PER_ITEM, nrows) - 1;
+        out.push_back({g, row0, c, last_row / p.group + 1});
+      }
+    }
+  std::stable_sort(out.begin(), out.end(), [](const WorkItem& a, const WorkItem& b) { return a.nkeys > b.nkeys; });
+}
+
+}  // namespace
+
+extern "C" {
+
+int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_out, size_t* workspace_bytes_out) {
+  if (plan_out) *plan_out = nullptr;
+  if (!desc || !plan_out || !workspace_bytes_out) return PA_ERR_NULL;
+  const int st = validate(desc);
+  if (st != PA_OK) return st;
+  prefix_attn_plan_t* p = new (std::nothrow) prefix_attn_plan_t();
+  if (!p) return PA_ERR_ALLOC;
+  try {
+    p->desc = *desc;
+    p->lens.assign(desc->suffix_lens, desc->suffix_lens + desc->num_rollouts);
+    p->desc.suffix_lens = p->lens.data();
+    p->cu.assign(desc->num_rollouts + 1, 0);
+    for (int g = 0; g < desc->num_rollouts; ++g) p->cu[g + 1] = p->cu[g] + p->lens[g];
+    p->T = p->cu.back();
+    p->group = desc->num_q_heads / desc->num_kv_heads;
+    build_prefix_items(*p);
+    build_suffix_items(*p);
+  } catch (const std::bad_alloc&) {
+    delete p;
+    return PA_ERR_ALLOC;
+  }
+  const size_t rows = (size_t)p->T * desc->num_q_heads;
+  const size_t o_bytes = align_up(rows * desc->head_dim * sizeof(float), 256);
+  const size_t l_bytes = align_up(rows * sizeof(float), 256);
+  p->off_o1 = 0;
+  p->off_o2 = o_bytes;
+  p->off_lse1 = 2 * o_bytes;
+  p->off_lse2 = p->off_lse1 + l_bytes;
+  p->off_lse = p->off_lse2 + l_bytes;
+  p->ws_bytes = p->off_lse + l_bytes;
+
+  if (desc->device >= 0) {
+    int prev = 0;
+    bool ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(desc->device) == hipSuccess;
+    if (ok) {
+      ok = hipMalloc((void**)&p->d_cu, p->cu.size() * sizeof(int32_t)) == hipSuccess &&
+           hipMemcpy(p->d_cu, p->cu.data(), p->cu.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+      for (int s = 0; ok && s < 2; ++s) {
+        if (p->items[s].empty()) continue;
+        const size_t bytes = p->items[s].size() * sizeof(WorkItem);
+        ok = hipMalloc((void**)&p->d_items[s], bytes) == hipSuccess &&
+             hipMemcpy(p->d_items[s], p->items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+      }
+      (void)hipSetDevice(prev);
+    }
+    if (!ok) {
+      (void)hipGetLastError();
+      prefix_attn_destroy(p);
+      return PA_ERR_ALLOC;
+    }
+  }
+  *plan_out = p;
+  *workspace_bytes_out = p->ws_bytes;
+  return PA_OK;
+}
+
+void prefix_attn_destroy(prefix_attn_plan_t* plan) {
+  if (!plan) return;
+  if (plan->d_cu) (void)hipFree(plan->d_cu);
+  for (int s = 0; s < 2; ++s)
+    if (plan->d_items[s]) (void)hipFree(plan->d_items[s]);
+  delete plan;
+}
+
+const char* prefix_attn_status_string(int status) {
+  switch (status) {
+    case PA_OK: return "ok";
+    case PA_ERR_NULL: return "a required pointer is NULL";
+    case PA_ERR_SHAPE: return "a size is out of range or inconsistent";
+    case PA_ERR_UNSUPPORTED: return "valid but unsupported configuration";
+    case PA_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case PA_ERR_WORKSPACE: return "workspace too small";
+    case PA_ERR_ALLOC: return "allocation failed";
+    case PA_ERR_HIP: return "HIP runtime call or kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_item, int32_t* keys_per_tile) {
+  if (!plan || !rows_per_item || !keys_per_tile) return PA_ERR_NULL;
+  *rows_per_item = pa::ROWS_PER_ITEM;
+  *keys_per_tile = pa::KEYS_PER_TILE;
+  return PA_OK;
+}
+
+int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass) {
+  if (!plan || pass < 0 || pass > 1) return -1;
+  return (int64_t)plan->items[pass].size();
+}
+
+int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out) {
+  if (!plan || !items_out) return PA_ERR_NULL;
+  if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
+  const std::vector<WorkItem>& v = plan->items[pass];
+  for (size_t n = 0; n < v.size(); ++n) {
+    items_out[4 * n + 0] = v[n].g;
+    items_out[4 * n + 1] = v[n].row0;
+    items_out[4 * n + 2] = v[n].c;
+    items_out[4 * n + 3] = v[n].nkeys;
+  }
+  return PA_OK;
+}
+
+int64_t prefix_attn_plan_total_tokens(const prefix_attn_plan_t* plan) { return plan ? plan->T : -1; }
+
+}  // extern "C"

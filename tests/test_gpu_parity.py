@@ -1,0 +1,90 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 oracle, element by element
+on the same seeded inputs.  Tolerances: out max-abs <= 2e-2 and mean-abs <= 2e-3,
+LSE max-abs <= 1e-3 (natural log)."""
+import numpy as np
+import pytest
+
+from oracle import cref
+from oracle import ref_attention as ref
+from paper_2507_07966_amd import workloads as wl
+from tests.gpu_util import check, run_hip
+
+pytestmark = pytest.mark.gpu
+
+
+def oracle_full(x, scale=None):
+    scale = x.workload.scale if scale is None else scale
+    o, l, _ = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens, scale)
+    return o, l
+
+
+def test_c1_tiny_fp32_full_tensor():
+    x = wl.make_inputs(wl.WORKLOADS["C1"])
+    out, lse = run_hip(x)
+    ro, rl = ref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens, x.workload.scale)
+    mx, _, ml = check(out, lse, ro, rl, "C1")
+    assert mx < 1e-5 and ml < 1e-5      # fp32 arithmetic: far inside the bf16 tolerances
+
+
+EDGE = [
+    # dtype, Hq, Hkv, D, P, suffix_lens
+    ("bf16", 28, 4, 128, 300, (70, 1, 129, 64)),     # ragged, P and S not multiples of any tile
+    ("bf16", 28, 4, 128, 0, (200, 37)),              # no prefix: plain packed causal attention
+    ("bf16", 4, 4, 128, 64, (1,)),                   # G = 1, S = 1, Hq = Hkv
+    ("bf16", 8, 1, 128, 1, (65, 64, 63)),            # single prefix key, one kv head
+    ("bf16", 14, 2, 64, 257, (100, 300)),            # head_dim 64
+    ("bf16", 7, 1, 128, 1000, (37,) * 5),            # one GQA group, many short rollouts
+    ("bf16", 2, 2, 128, 129, (513,)),                # rows cross several work items with group = 1
+    ("f32", 4, 2, 64, 100, (33, 70)),
+    ("f32", 6, 2, 128, 0, (50, 1)),
+    ("f32", 3, 3, 128, 65, (1, 2, 3)),
+]
+
+
+@pytest.mark.parametrize("dtype,Hq,Hkv,D,P,lens", EDGE)
+def test_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
+    x = wl.make_custom(dtype, Hq, Hkv, D, P, lens, seed=3)
+    print(f"edge case {dtype} Hq={Hq} Hkv={Hkv} D={D} P={P} lens={lens}", flush=True)
+    out, lse = run_hip(x)
+    ro, rl = oracle_full(x)
+    check(out, lse, ro, rl, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
+
+
+def test_large_scores_and_late_maximum():
+    """Scores with a wide range, and the largest keys at the very end of the prefix, so the
+    running reference maximum has to move late and by a lot."""
+    x = wl.make_custom("bf16", 14, 2, 128, 700, (150, 90), seed=5, std=2.5)
+    x.k_prefix[-3:] *= 3.0
+    x.bits["k_prefix"], x.k_prefix = wl.round_to_bf16(x.k_prefix)
+    out, lse = run_hip(x)
+    ro, rl = oracle_full(x)
+    check(out, lse, ro, rl, "late maximum")
+
+
+def test_uniform_scores_give_mean_of_v_on_gpu():
+    x = wl.make_custom("bf16", 4, 2, 128, 200, (30, 77), seed=6)
+    x.q[...] = 0
+    x.bits["q"][...] = 0
+    out, lse = run_hip(x)
+    off = ref.suffix_offsets(x.suffix_lens)
+    for g in range(2):
+        for i in (0, x.suffix_lens[g] - 1):
+            t = off[g] + i
+            for h in range(4):
+                vis = np.concatenate([x.v_prefix[:, h // 2], x.v_suffix[off[g]:t + 1, h // 2]]).astype(np.float64)
+                assert np.abs(out[t, h] - vis.mean(axis=0)).max() < 2e-3
+                assert abs(lse[h, t] - np.log(200 + i + 1)) < 1e-4
+
+
+def test_bitwise_reproducible():
+    x = wl.make_custom("bf16", 28, 4, 128, 500, (300, 129), seed=7)
+    a = run_hip(x)
+    b = run_hip(x)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_c2_full_tensor():
+    x = wl.make_inputs(wl.WORKLOADS["C2"])
+    out, lse = run_hip(x)
+    ro, rl = oracle_full(x)
+    check(out, lse, ro, rl, "C2")

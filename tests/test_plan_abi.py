@@ -1,0 +1,142 @@
+"""CPU-only tests of the C-ABI library: it loads, exports what the header declares,
+rejects bad arguments before any launch, and its schedule covers every visible
+(query row, key) pair exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2507_07966_amd as pa
+from paper_2507_07966_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "prefix_attn.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(prefix_attn_\w+)\s*\(", header))
+    assert {"prefix_attn_plan", "prefix_attn_forward", "prefix_attn_lse", "prefix_attn_destroy"} <= declared
+    lib = ctypes.CDLL(binding.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+
+
+def host_plan(**kw):
+    args = dict(num_q_heads=28, num_kv_heads=4, head_dim=128, prefix_len=4096, suffix_lens=[1152] * 8,
+                softmax_scale=128 ** -0.5, dtype="bf16", device=-1)
+    args.update(kw)
+    return pa.prefix_attn_plan(**args)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(num_q_heads=0), 2), (dict(num_kv_heads=3), 2), (dict(prefix_len=-1), 2), (dict(suffix_lens=[]), 2),
+    (dict(suffix_lens=[5, 0, 3]), 2), (dict(softmax_scale=0.0), 2), (dict(softmax_scale=float("nan")), 2),
+    (dict(softmax_scale=float("inf")), 2), (dict(head_dim=96), 3), (dict(dtype=7), 3), (dict(device=-2), 2),
+    (dict(prefix_len=(1 << 30) + 1), 2),
+])
+def test_plan_rejects_bad_descriptors(kw, status):
+    with pytest.raises(pa.PrefixAttnError) as e:
+        host_plan(**kw)
+    assert e.value.status == status
+
+
+def test_null_arguments_and_status_strings():
+    lib = binding.load_library()
+    assert lib.prefix_attn_plan(None, None, None) == 1
+    assert lib.prefix_attn_forward(None, None, None, None, None, None, None, None, 0, None) == 1
+    assert lib.prefix_attn_lse(None, None, None, None) == 1
+    lib.prefix_attn_destroy(None)
+    assert lib.prefix_attn_plan_num_items(None, 0) == -1
+    for s in range(8):
+        assert pa.prefix_attn_status_string(s) not in ("", "unknown status")
+    assert pa.prefix_attn_status_string(99) == "unknown status"
+
+
+def test_forward_checks_arguments_before_launch():
+    """With a host-only plan nothing can be launched; the checks must fire in order without touching memory."""
+    plan = host_plan()
+    lib = binding.load_library()
+    a = 0x10000  # fake, 16-byte aligned "device" addresses: never dereferenced by the checks
+    f = lambda *p: lib.prefix_attn_forward(plan.handle, *p)
+    big = plan.workspace_bytes
+    assert f(None, a, a, a, a, a, a, big, None) == 1
+    assert f(a, None, a, a, a, a, a, big, None) == 1          # prefix needed when P > 0
+    assert f(a, a, a, a, a, a, None, big, None) == 1
+    assert f(a + 8, a, a, a, a, a, a, big, None) == 4
+    assert f(a, a, a, a, a + 2, a, a, big, None) == 4
+    assert f(a, a, a, a, a, a, a, big - 1, None) == 5
+    assert f(a, a, a, a, a, a, a, big, None) == 3             # host-only plan cannot launch
+    assert lib.prefix_attn_lse(plan.handle, a, a + 4, None) == 4
+    assert lib.prefix_attn_lse(plan.handle, a, a, None) == 3
+    noprefix = host_plan(prefix_len=0)
+    assert lib.prefix_attn_forward(noprefix.handle, a, None, None, a, a, a, a, noprefix.workspace_bytes, None) == 3
+
+
+def test_workspace_size_matches_layout():
+    plan = host_plan()
+    T, Hq, D = 1152 * 8, 28, 128
+    assert plan.total_tokens == T
+    need = 2 * T * Hq * D * 4 + 3 * T * Hq * 4
+    assert need <= plan.workspace_bytes <= need + 5 * 256
+
+
+def coverage(plan, Hq, Hkv, P, lens):
+    """Count how often each (kv head, rollout, stacked row) is covered by each pass and check key extents."""
+    r = Hq // Hkv
+    bm, bn = plan.tiles()
+    assert bm > 0 and bn > 0
+    for which in (0, 1):
+        items = plan.items(which)
+        seen = [[np.zeros(S * r, dtype=np.int32) for S in lens] for _ in range(Hkv)]
+        for g, row0, c, nkeys in items:
+            if g < 0:
+                continue
+            assert 0 <= g < len(lens) and 0 <= c < Hkv and row0 % bm == 0
+            n = lens[g] * r
+            assert row0 < n
+            hi = min(row0 + bm, n)
+            seen[c][g][row0:hi] += 1
+            if which == 0:
+                assert nkeys == P                        # the whole prefix rectangle, no mask
+            else:
+                last_pos = (hi - 1) // r
+                assert nkeys == last_pos + 1             # keys 0..position of the item's last row
+                assert nkeys <= lens[g]
+        if which == 0 and P == 0:
+            assert len(items) == 0
+            continue
+        for c in range(Hkv):
+            for g in range(len(lens)):
+                assert (seen[c][g] == 1).all(), (which, c, g)
+
+
+@pytest.mark.parametrize("Hq,Hkv,P,lens", [
+    (28, 4, 4096, [1152] * 8), (28, 4, 100, [1, 37, 300, 5]), (4, 4, 0, [70, 3]), (8, 1, 64, [64]),
+    (6, 3, 1000, [257, 256, 255]), (16, 16, 130, [33] * 5),
+])
+def test_schedule_covers_every_pair_exactly_once(Hq, Hkv, P, lens):
+    plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
+    coverage(plan, Hq, Hkv, P, lens)
+
+
+def test_prefix_items_are_grouped_by_kv_head_per_xcd():
+    """Workgroup n runs on XCD n % 8: with 4 kv heads each XCD must only ever see one kv head."""
+    plan = host_plan()
+    items = plan.items(0)
+    for x in range(8):
+        heads = {int(c) for g, _, c, _ in items[x::8] if g >= 0}
+        assert len(heads) == 1
+    # suffix pass is issued longest first
+    nk = plan.items(1)[:, 3]
+    assert (np.diff(nk) <= 0).all()
+
+
+def test_c5_ragged_plan_builds_fast():
+    rng = np.random.default_rng(0)
+    lens = (512 + rng.integers(256, 4097, size=16)).tolist()
+    plan = host_plan(prefix_len=8192 * 64, suffix_lens=lens)
+    coverage(plan, 28, 4, 8192 * 64, lens)
