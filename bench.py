@@ -1,0 +1,177 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-shared GRPO prefill attention hot path on one MI355X.
+
+One "step" = one pass of the whole hot path (prefix pass + suffix pass + merge + LSE export)
+over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+
+metric  : effective attention TFLOP/s = 4 D Hq sum_g[S_g P + S_g (S_g + 1) / 2] / time
+roofline: the prefix pass (the dominant kernel) against the published dense bf16 MFMA peak
+cpu_baseline: the fp64 C oracle on this host's cores, on a bounded sample of the same
+          workload's query rows (also used as a parity spot check of the GPU result)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2507_07966_amd as pa
+    from paper_2507_07966_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    pa.load_library()   # fails loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+
+    w = wl.WORKLOADS[args.workload]
+    x = wl.make_inputs(w)
+    T, P = x.total_suffix, w.prefix_len
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def up(name):
+        if w.dtype == "bf16":
+            return torch.from_numpy(x.bits[name].view(np.int16)).cuda().view(torch.bfloat16)
+        return torch.from_numpy(getattr(x, name)).cuda()
+
+    dev = {n: up(n) for n in ("q", "k_prefix", "v_prefix", "k_suffix", "v_suffix")}
+    t0 = time.perf_counter()
+    plan = pa.prefix_attn_plan(w.num_q_heads, w.num_kv_heads, w.head_dim, P, x.suffix_lens, w.scale, dtype=w.dtype, device=0)
+    plan_ms = (time.perf_counter() - t0) * 1e3
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.empty((T, w.num_q_heads, w.head_dim), dtype=tdt, device="cuda")
+    lse = torch.empty((w.num_q_heads, T), dtype=torch.float32, device="cuda")
+    fwd_args = (plan, dev["q"], dev["k_prefix"] if P else None, dev["v_prefix"] if P else None, dev["k_suffix"],
+                dev["v_suffix"], out, ws)
+
+    def step():
+        pa.prefix_attn_forward(*fwd_args)
+        pa.prefix_attn_lse(plan, ws, lse)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record()
+    for i in range(args.steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per_step = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)])
+    ms_per_step = float(ev[0].elapsed_time(ev[args.steps]) / args.steps)
+
+    # per-kernel durations over the same number of steps (HIP events on the launch stream)
+    kms = np.array([pa.prefix_attn_forward_timed(*fwd_args) for _ in range(args.steps)])
+    k_prefix_ms, k_suffix_ms, k_merge_ms = (float(v) for v in kms.mean(axis=0))
+
+    flop = wl.effective_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
+    tflops = flop / (ms_per_step * 1e-3) * 1e-12
+    prefix_flop = 4 * w.head_dim * w.num_q_heads * T * P
+    suffix_flop = flop - prefix_flop
+    if P:
+        dom_name, dom_flop, dom_ms = "prefix_pass", prefix_flop, k_prefix_ms
+    else:
+        dom_name, dom_flop, dom_ms = "suffix_pass", suffix_flop, k_suffix_ms
+    achieved = dom_flop / (dom_ms * 1e-3) * 1e-12
+    e = 2 if w.dtype == "bf16" else 4
+    merge_bytes = T * w.num_q_heads * (w.head_dim * (8 + e) + 12)
+    result = {
+        "metric": "effective attention TFLOP/s",
+        "value": round(tflops, 2),
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}", "num_q_heads": w.num_q_heads, "num_kv_heads": w.num_kv_heads,
+                   "head_dim": w.head_dim, "prefix_len": P, "prompt_len": w.prompt_len,
+                   "num_rollouts": w.num_rollouts, "total_suffix_tokens": T,
+                   "suffix_lens_min_max": [int(x.suffix_lens.min()), int(x.suffix_lens.max())]},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "tokens_per_s_suffix": round(T / (ms_per_step * 1e-3), 1),
+        "tokens_per_s_equiv_full_prefill": round(float(np.sum(P + x.suffix_lens.astype(np.int64))) / (ms_per_step * 1e-3), 1),
+        "effective_flop": flop,
+        "ms_median": round(float(np.median(per_step)), 4),
+        "wall_ms_per_step": round(wall_ms / args.steps, 4),
+        "plan_ms": round(plan_ms, 3),
+        "kernel_ms": {"prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
+        "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1),
+        "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import cref
+        rows_all = wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 4, seed=1)
+        rng = np.random.default_rng(2)
+        rng.shuffle(rows_all)
+
+        def run_oracle(rows):
+            t = time.perf_counter()
+            o, l, thr = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
+                                                     x.suffix_lens, w.scale, rows=rows)
+            return o, l, thr, time.perf_counter() - t
+
+        off = np.concatenate([[0], np.cumsum(x.suffix_lens.astype(np.int64))])
+
+        def pairs_of(rows):
+            g = np.searchsorted(off, rows, side="right") - 1
+            return int(np.sum(P + (rows - off[g]) + 1))
+
+        probe = rows_all[:2]
+        _, _, thr, t_probe = run_oracle(probe)
+        n = int(max(2, min(len(rows_all), args.cpu_seconds / max(t_probe / 2, 1e-6))))
+        rows = np.sort(rows_all[:n])
+        o_ref, l_ref, thr, t_cpu = run_oracle(rows)
+        cpu_flop = 4 * w.head_dim * w.num_q_heads * pairs_of(rows)
+        o_gpu = out[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        l_gpu = lse[:, torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+        result["cpu_baseline"] = {
+            "value": round(cpu_flop / t_cpu * 1e-12, 6), "unit": "TFLOP/s", "cores": int(thr), "kind": "oracle",
+            "sample": f"{len(rows)} seeded query rows x {w.num_q_heads} heads of {w.name} against their full key sets "
+                      f"(fp64, {t_cpu:.1f} s)",
+            "seconds": round(t_cpu, 2),
+            "extrapolated_full_workload_seconds": round(t_cpu * flop / cpu_flop, 1),
+        }
+        result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - o_ref).max()),
+                                      "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
+                                      "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -92,6 +92,16 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
                         const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* Measurement variant of prefix_attn_forward: same arguments and result, but each of the
+ * three kernels is bracketed by HIP events on `hip_stream` and the call WAITS for them.
+ * kernel_ms (HOST [3]) receives the durations in milliseconds of {prefix pass, suffix pass,
+ * merge}; the prefix entry is 0 when P == 0.  Creates and destroys events, so it is not for
+ * stream capture or latency-critical loops. */
+int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                              const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                              void* out, void* workspace, size_t workspace_bytes, void* hip_stream,
+                              float* kernel_ms);
+
 /* Copy the merged log-sum-exp (natural log, fp32) of the last forward call that used
  * `workspace` into lse_out [Hq, T].  Must be enqueued after that forward call on the
  * same stream (or otherwise ordered after it); calling it on a workspace that no

@@ -6,7 +6,7 @@ use and raises if the library has not been built.
 """
 from . import workloads  # noqa: F401
 
-_BINDING_NAMES = ("PrefixAttnPlan", "PrefixAttnError", "prefix_attn_plan", "prefix_attn_forward",
+_BINDING_NAMES = ("PrefixAttnPlan", "PrefixAttnError", "prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed",
                   "prefix_attn_lse", "prefix_attn_destroy", "prefix_attn_status_string",
                   "library_path", "load_library")
 

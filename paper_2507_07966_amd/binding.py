@@ -20,7 +20,7 @@ _lib = None
 PA_F32, PA_BF16 = 0, 1
 STATUS_NAMES = {0: "PA_OK", 1: "PA_ERR_NULL", 2: "PA_ERR_SHAPE", 3: "PA_ERR_UNSUPPORTED", 4: "PA_ERR_ALIGN",
                 5: "PA_ERR_WORKSPACE", 6: "PA_ERR_ALLOC", 7: "PA_ERR_HIP"}
-EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_lse", "prefix_attn_destroy",
+EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed", "prefix_attn_lse", "prefix_attn_destroy",
                     "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
                     "prefix_attn_plan_items", "prefix_attn_plan_total_tokens")
 
@@ -56,6 +56,8 @@ def load_library():
     lib.prefix_attn_plan.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp), ctypes.POINTER(sz)]
     lib.prefix_attn_forward.restype = ctypes.c_int
     lib.prefix_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prefix_attn_forward_timed.restype = ctypes.c_int
+    lib.prefix_attn_forward_timed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.prefix_attn_lse.restype = ctypes.c_int
     lib.prefix_attn_lse.argtypes = [vp, vp, vp, vp]
     lib.prefix_attn_destroy.restype = None
@@ -176,6 +178,19 @@ def prefix_attn_forward(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v
                                             _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream))
     if st:
         raise PrefixAttnError(st, "prefix_attn_forward")
+
+
+def prefix_attn_forward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace,
+                              stream=None):
+    """prefix_attn_forward_timed of the C ABI.  Waits; returns (prefix_ms, suffix_ms, merge_ms)."""
+    ws_bytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else plan.workspace_bytes
+    ms = (ctypes.c_float * 3)()
+    st = load_library().prefix_attn_forward_timed(plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix),
+                                                  _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes,
+                                                  _stream(stream), ms)
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_forward_timed")
+    return float(ms[0]), float(ms[1]), float(ms[2])
 
 
 def prefix_attn_lse(plan: PrefixAttnPlan, workspace, lse_out, stream=None) -> None:

@@ -9,13 +9,11 @@ namespace {
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-}  // namespace
-
-extern "C" {
-
-int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
-                        const void* k_suffix, const void* v_suffix, void* out, void* workspace,
-                        size_t workspace_bytes, void* hip_stream) {
+// Checks, then the three launches.  When `ev` is non-null it holds 4 events recorded before
+// the prefix pass, between the kernels and after the merge.
+int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
+                    const void* k_suffix, const void* v_suffix, void* out, void* workspace, size_t workspace_bytes,
+                    void* hip_stream, hipEvent_t* ev) {
   if (!plan || !q || !k_suffix || !v_suffix || !out || !workspace) return PA_ERR_NULL;
   const prefix_attn_desc_t& d = plan->desc;
   const bool has_prefix = d.prefix_len > 0;
@@ -45,6 +43,8 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
   a.scale = d.softmax_scale;
   auto launch_pass = (d.dtype == PA_BF16) ? pa::launch_pass_bf16 : pa::launch_pass_f32;
 
+  hipStream_t hs = static_cast<hipStream_t>(hip_stream);
+  if (ev && hipEventRecord(ev[0], hs) != hipSuccess) return PA_ERR_HIP;
   if (has_prefix) {
     a.k = k_prefix;
     a.v = v_prefix;
@@ -55,6 +55,7 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
     a.causal = false;
     if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
   }
+  if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;
   a.k = k_suffix;
   a.v = v_suffix;
   a.o_part = o2;
@@ -64,6 +65,7 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
   a.causal = true;
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 
+  if (ev && hipEventRecord(ev[2], hs) != hipSuccess) return PA_ERR_HIP;
   pa::MergeArgs m{};
   m.o1 = o1;
   m.lse1 = lse1;
@@ -76,7 +78,37 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
   m.dtype = d.dtype;
   m.has_prefix = has_prefix;
   if (pa::launch_merge(m, hip_stream) != 0) return PA_ERR_HIP;
+  if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
   return PA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
+                        const void* k_suffix, const void* v_suffix, void* out, void* workspace,
+                        size_t workspace_bytes, void* hip_stream) {
+  return enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace, workspace_bytes, hip_stream,
+                         nullptr);
+}
+
+int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                              const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
+                              void* workspace, size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
+  if (!kernel_ms) return PA_ERR_NULL;
+  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  int st = PA_OK;
+  for (int i = 0; i < 4 && st == PA_OK; ++i)
+    if (hipEventCreate(&ev[i]) != hipSuccess) st = PA_ERR_HIP;
+  if (st == PA_OK)
+    st = enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace, workspace_bytes, hip_stream, ev);
+  if (st == PA_OK && hipEventSynchronize(ev[3]) != hipSuccess) st = PA_ERR_HIP;
+  for (int i = 0; i < 3 && st == PA_OK; ++i)
+    if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = PA_ERR_HIP;
+  for (int i = 0; i < 4; ++i)
+    if (ev[i]) (void)hipEventDestroy(ev[i]);
+  return st;
 }
 
 int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out, void* hip_stream) {
