@@ -91,7 +91,7 @@ def main():
 
     # per-kernel durations over the same number of steps (HIP events on the launch stream)
     kms = np.array([pa.prefix_attn_forward_timed(*fwd_args) for _ in range(args.steps)])
-    k_prefix_ms, k_suffix_ms, k_merge_ms = (float(v) for v in kms.mean(axis=0))
+    k_prepass_ms, k_prefix_ms, k_suffix_ms, k_merge_ms = (float(v) for v in kms.mean(axis=0))
 
     flop = wl.effective_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
@@ -128,7 +128,7 @@ def main():
         "ms_median": round(float(np.median(per_step)), 4),
         "wall_ms_per_step": round(wall_ms / args.steps, 4),
         "plan_ms": round(plan_ms, 3),
-        "kernel_ms": {"prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
+        "kernel_ms": {"v_layout_prepass": round(k_prepass_ms, 4), "prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
         "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1),
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},

@@ -15,7 +15,8 @@
  *
  *   The library computes this as three kernels: a prefix pass (no mask; all rollouts'
  *   rows of one kv head stacked against LDS-staged prefix K/V tiles), a causal suffix
- *   pass, and a log-sum-exp merge of the two partial results.
+ *   pass, and a log-sum-exp merge of the two partial results.  On the bf16 path a small
+ *   layout pre-pass first rewrites V into transposed, LDS-ready tile images.
  *
  * Conventions
  *   - No C++ types, no exceptions and no printing cross this boundary.  Every call
@@ -86,17 +87,18 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
  *   v_suffix  [T, Hkv, D]  per-rollout prompt+response values
  *   out       [T, Hq,  D]  attention output, same dtype as q
  *   workspace              scratch of at least the planned size; holds the two fp32
- *                          partial results and the merged LSE after the call
+ *                          partial results, the merged LSE and (bf16) the V tile images
  * Argument errors are reported before anything is launched. */
 int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                         const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Measurement variant of prefix_attn_forward: same arguments and result, but each of the
- * three kernels is bracketed by HIP events on `hip_stream` and the call WAITS for them.
- * kernel_ms (HOST [3]) receives the durations in milliseconds of {prefix pass, suffix pass,
- * merge}; the prefix entry is 0 when P == 0.  Creates and destroys events, so it is not for
- * stream capture or latency-critical loops. */
+ * launches is bracketed by HIP events on `hip_stream` and the call WAITS for them.
+ * kernel_ms (HOST [4]) receives the durations in milliseconds of {V layout pre-pass, prefix
+ * pass, suffix pass, merge}; the prefix entry is ~0 when P == 0 and the pre-pass entry is ~0
+ * for fp32 plans.  Creates and destroys events, so it is not for stream capture or
+ * latency-critical loops. */
 int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                               const void* v_prefix, const void* k_suffix, const void* v_suffix,
                               void* out, void* workspace, size_t workspace_bytes, void* hip_stream,

@@ -182,15 +182,15 @@ def prefix_attn_forward(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v
 
 def prefix_attn_forward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace,
                               stream=None):
-    """prefix_attn_forward_timed of the C ABI.  Waits; returns (prefix_ms, suffix_ms, merge_ms)."""
+    """prefix_attn_forward_timed of the C ABI.  Waits; returns (prepass_ms, prefix_ms, suffix_ms, merge_ms)."""
     ws_bytes = workspace.numel() * workspace.element_size() if hasattr(workspace, "numel") else plan.workspace_bytes
-    ms = (ctypes.c_float * 3)()
+    ms = (ctypes.c_float * 4)()
     st = load_library().prefix_attn_forward_timed(plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix),
                                                   _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes,
                                                   _stream(stream), ms)
     if st:
         raise PrefixAttnError(st, "prefix_attn_forward_timed")
-    return float(ms[0]), float(ms[1]), float(ms[2])
+    return float(ms[0]), float(ms[1]), float(ms[2]), float(ms[3])
 
 
 def prefix_attn_lse(plan: PrefixAttnPlan, workspace, lse_out, stream=None) -> None:

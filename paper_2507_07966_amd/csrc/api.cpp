@@ -9,8 +9,8 @@ namespace {
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-// Checks, then the three launches.  When `ev` is non-null it holds 4 events recorded before
-// the prefix pass, between the kernels and after the merge.
+// Checks, then the launches (layout pre-pass, prefix pass, suffix pass, merge).  When `ev` is
+// non-null it holds 5 events recorded before, between and after them.
 int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
                     const void* k_suffix, const void* v_suffix, void* out, void* workspace, size_t workspace_bytes,
                     void* hip_stream, hipEvent_t* ev) {
@@ -45,9 +45,29 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
 
   hipStream_t hs = static_cast<hipStream_t>(hip_stream);
   if (ev && hipEventRecord(ev[0], hs) != hipSuccess) return PA_ERR_HIP;
+  if (d.dtype == PA_BF16) {  // layout pre-pass: V^T tile images for the MFMA passes
+    pa::VtArgs t{};
+    t.v_prefix = v_prefix;
+    t.v_suffix = v_suffix;
+    t.vt_prefix = ws + plan->off_vtp;
+    t.vt_suffix = ws + plan->off_vts;
+    t.cu = plan->d_cu;
+    t.vt_off = plan->d_vt_off;
+    t.P = d.prefix_len;
+    t.tiles_prefix = plan->tiles_prefix;
+    t.tiles_suffix = plan->tiles_suffix;
+    t.G = d.num_rollouts;
+    t.Hkv = d.num_kv_heads;
+    t.D = d.head_dim;
+    if (pa::launch_vt_images(t, hip_stream) != 0) return PA_ERR_HIP;
+  }
+  if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;
   if (has_prefix) {
     a.k = k_prefix;
     a.v = v_prefix;
+    a.vt = ws + plan->off_vtp;
+    a.vt_off = nullptr;
+    a.vt_tiles_per_head = plan->tiles_prefix;
     a.o_part = o1;
     a.lse_part = lse1;
     a.items = plan->d_items[0];
@@ -55,9 +75,12 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     a.causal = false;
     if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
   }
-  if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;
+  if (ev && hipEventRecord(ev[2], hs) != hipSuccess) return PA_ERR_HIP;
   a.k = k_suffix;
   a.v = v_suffix;
+  a.vt = ws + plan->off_vts;
+  a.vt_off = plan->d_vt_off;
+  a.vt_tiles_per_head = plan->tiles_suffix;
   a.o_part = o2;
   a.lse_part = lse2;
   a.items = plan->d_items[1];
@@ -65,7 +88,7 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   a.causal = true;
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 
-  if (ev && hipEventRecord(ev[2], hs) != hipSuccess) return PA_ERR_HIP;
+  if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
   pa::MergeArgs m{};
   m.o1 = o1;
   m.lse1 = lse1;
@@ -78,7 +101,7 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   m.dtype = d.dtype;
   m.has_prefix = has_prefix;
   if (pa::launch_merge(m, hip_stream) != 0) return PA_ERR_HIP;
-  if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
+  if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
   return PA_OK;
 }
 
@@ -97,16 +120,16 @@ int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, con
                               const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
                               void* workspace, size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
   if (!kernel_ms) return PA_ERR_NULL;
-  hipEvent_t ev[4] = {nullptr, nullptr, nullptr, nullptr};
+  hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
   int st = PA_OK;
-  for (int i = 0; i < 4 && st == PA_OK; ++i)
+  for (int i = 0; i < 5 && st == PA_OK; ++i)
     if (hipEventCreate(&ev[i]) != hipSuccess) st = PA_ERR_HIP;
   if (st == PA_OK)
     st = enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace, workspace_bytes, hip_stream, ev);
-  if (st == PA_OK && hipEventSynchronize(ev[3]) != hipSuccess) st = PA_ERR_HIP;
-  for (int i = 0; i < 3 && st == PA_OK; ++i)
+  if (st == PA_OK && hipEventSynchronize(ev[4]) != hipSuccess) st = PA_ERR_HIP;
+  for (int i = 0; i < 4 && st == PA_OK; ++i)
     if (hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]) != hipSuccess) st = PA_ERR_HIP;
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 5; ++i)
     if (ev[i]) (void)hipEventDestroy(ev[i]);
   return st;
 }

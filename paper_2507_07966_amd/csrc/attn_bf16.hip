@@ -8,18 +8,23 @@
 // the same prefix keys/values; only the prompt+response part differs (Sec. 4.2, Sec. 5.2).
 //
 // Mapping onto the hardware
-//   - A workgroup (4 wavefronts) owns ROWS_PER_ITEM = 256 stacked rows m = i * group + (h % group) of one
-//     (kv head, rollout): all q heads of a GQA group and consecutive positions are stacked,
-//     so every K/V tile staged in LDS is used by 256 rows.  Each wavefront owns 64 rows.
+//   - A workgroup (4 wavefronts) owns ROWS_PER_ITEM = 128 stacked rows
+//     m = i * group + (h % group) of one (kv head, rollout): the q heads of a GQA group and
+//     consecutive positions are stacked, so every K/V tile staged in LDS serves 128 rows.
+//     Each wavefront owns 32 rows.  Two workgroups share a CU (<= 256 registers, 64 KiB LDS
+//     each), so one wavefront's softmax VALU work overlaps the other's MFMA work.
+//   - K tiles and the pre-transposed V tile images go global -> LDS with direct-to-LDS
+//     16-byte loads (no staging registers), double buffered, one barrier per tile.  The LDS
+//     layouts are XOR-swizzled so every 16-byte operand read is bank-conflict free.
 //   - Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: the
-//     accumulator then holds, per lane, 16 keys of ONE query column, so the row maximum and
-//     row sum are in-register plus one exchange between lane l and lane l+32, and the
-//     probabilities are already laid out as the B operand of O^T += V^T P^T.
-//   - V is staged row-major ([key][d]) and read with the LDS transpose load
-//     (ds_read_b64_tr_b16), which hands each lane 4 consecutive keys of one channel d.
+//     accumulator then holds, per lane, 16 keys of ONE query column, so the row maximum is
+//     in-register plus one exchange between lane l and lane l+32, and the probabilities are
+//     already laid out as the B operand of O^T += V^T P^T.
 //   - Online softmax with a lazily updated reference maximum: the accumulators are rescaled
 //     only when some row's maximum exceeds the reference by more than 2^8, which keeps every
-//     probability below 2^8 (exact in fp32/bf16 range) and removes almost all rescaling work.
+//     probability below 2^8 (harmless in fp32/bf16) and removes almost all rescaling work.
+//     The row sum is accumulated in fp32 from the unrounded probabilities, which keeps the
+//     LSE error at fp32 level even for rows that see only a few keys.
 #include <hip/hip_runtime.h>
 
 #include "common.h"
@@ -32,67 +37,33 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 #define LDS_PTR(T) __attribute__((address_space(3))) T*
+#define GLB_PTR(T) __attribute__((address_space(1))) T*
 
-constexpr int BN = KEYS_PER_TILE;   // keys per LDS tile
+constexpr int BN = KEYS_PER_TILE;  // keys per LDS tile
 constexpr int NTHREADS = 256;
+constexpr int ROWS_PER_WAVE = ROWS_PER_ITEM / 4;
+static_assert(ROWS_PER_WAVE == 32, "one 32-column MFMA block of queries per wavefront");
 constexpr float RESCALE_LOG2 = 8.0f;  // lazy-rescale threshold in log2 units
 
+// LDS stage: K tile [64 keys][D] (rows of D*2 bytes) followed by the V^T image [D][64 slots]
+// (rows of 128 bytes).  16-byte chunk j of a row r is stored at chunk position
+//   j ^ (r & 15)          for 256-byte rows,
+//   j ^ ((r >> 1) & 7)    for 128-byte rows,
+// so that 16 consecutive rows read at the same logical chunk cover all 64 banks.
 template <int D>
-struct Lds {
-  // Row strides in bytes.  K rows are read 16 B per lane by 32 different keys at the same
-  // channel offset: stride = 16 (mod 256) spreads 16 keys over all 64 banks.  V rows are read
-  // 8 B per lane by 4 keys x 64 contiguous bytes per half-wave: stride = 64 (mod 256).
-  static constexpr int KSTRIDE = D * 2 + 16;
-  static constexpr int VSTRIDE = D * 2 + 64;
-  static constexpr int KBYTES = BN * KSTRIDE;
-  static constexpr int VBYTES = BN * VSTRIDE;
+struct Tile {
+  static constexpr int ROWB = D * 2;
+  static constexpr int KBYTES = BN * ROWB;
+  static constexpr int VBYTES = D * 128;
   static constexpr int STAGE = KBYTES + VBYTES;
-  static constexpr int TOTAL = 2 * STAGE;
+  static constexpr int KBLOCKS_PER_WAVE = KBYTES / 1024 / 4;  // 1 KiB per wavefront-wide load
+  static constexpr int VBLOCKS_PER_WAVE = VBYTES / 1024 / 4;
 };
 
-// One K or V tile in flight from global memory to LDS: each thread carries PASSES x 16 bytes.
-template <int D>
-struct TileRegs {
-  static constexpr int LANES_PER_ROW = D / 8;                // 16-byte pieces per row
-  static constexpr int ROWS_PER_PASS = NTHREADS / LANES_PER_ROW;
-  static constexpr int PASSES = BN / ROWS_PER_PASS;
-  u32x4 k[PASSES], v[PASSES];
-};
-
-template <int D>
-__device__ inline void load_tile(TileRegs<D>& t, const __bf16* __restrict__ kbase, const __bf16* __restrict__ vbase,
-                                 int64_t row_stride, int key0, int nkeys, int tid) {
-  constexpr int LPR = TileRegs<D>::LANES_PER_ROW;
-  const int r0 = tid / LPR, col = (tid % LPR) * 8;
-#pragma unroll
-  for (int p = 0; p < TileRegs<D>::PASSES; ++p) {
-    const int key = key0 + r0 + p * TileRegs<D>::ROWS_PER_PASS;
-    if (key < nkeys) {
-      t.k[p] = *reinterpret_cast<const u32x4*>(kbase + key * row_stride + col);
-      t.v[p] = *reinterpret_cast<const u32x4*>(vbase + key * row_stride + col);
-    } else {  // rows past the end are zero so that masked probabilities meet finite values
-      t.k[p] = u32x4{0, 0, 0, 0};
-      t.v[p] = u32x4{0, 0, 0, 0};
-    }
-  }
-}
-
-template <int D>
-__device__ inline void store_tile(const TileRegs<D>& t, unsigned char* stage, int tid) {
-  constexpr int LPR = TileRegs<D>::LANES_PER_ROW;
-  const int r0 = tid / LPR, colb = (tid % LPR) * 16;
-#pragma unroll
-  for (int p = 0; p < TileRegs<D>::PASSES; ++p) {
-    const int row = r0 + p * TileRegs<D>::ROWS_PER_PASS;
-    *reinterpret_cast<u32x4*>(stage + row * Lds<D>::KSTRIDE + colb) = t.k[p];
-    *reinterpret_cast<u32x4*>(stage + Lds<D>::KBYTES + row * Lds<D>::VSTRIDE + colb) = t.v[p];
-  }
-}
+__device__ inline int swizzle_term(int row, int rowb) { return rowb == 256 ? (row & 15) : ((row >> 1) & 7); }
 
 // Exchange between lane l and lane l^32 with v_permlane32_swap.  The two results are read
 // through named unsigned temporaries: bit-casting the builtin's vector elements directly was
@@ -115,19 +86,20 @@ __device__ inline float pair_sum(float x) {
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS) void pass_bf16_kernel(const __bf16* __restrict__ q, const __bf16* __restrict__ k,
-                                                             const __bf16* __restrict__ v, float* __restrict__ o_part,
-                                                             float* __restrict__ lse_part,
-                                                             const WorkItem* __restrict__ items,
-                                                             const int32_t* __restrict__ cu, int Hq, int Hkv, int group,
-                                                             float scale) {
+__global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
+    const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
+    float* __restrict__ o_part, float* __restrict__ lse_part, const WorkItem* __restrict__ items,
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head, int Hq, int Hkv,
+    int group, float scale) {
+  using TL = Tile<D>;
   constexpr int KK = D / 16;  // contraction steps of QK^T
   constexpr int DB = D / 32;  // 32-channel blocks of the output
-  __shared__ __attribute__((aligned(16))) unsigned char smem[Lds<D>::TOTAL];
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * TL::STAGE];
 
   const WorkItem it = items[blockIdx.x];
   if (it.g < 0) return;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int off_g = cu[it.g];
   const int S_g = cu[it.g + 1] - off_g;
@@ -135,71 +107,99 @@ __global__ __launch_bounds__(NTHREADS) void pass_bf16_kernel(const __bf16* __res
   const int nkeys = it.nkeys;
   const int64_t row_stride = (int64_t)Hkv * D;
   const __bf16* kbase = k + ((int64_t)(CAUSAL ? off_g : 0) * Hkv + it.c) * D;
-  const __bf16* vbase = v + ((int64_t)(CAUSAL ? off_g : 0) * Hkv + it.c) * D;
+  const __bf16* vtbase = vt + ((int64_t)it.c * vt_tiles_per_head + (CAUSAL ? vt_off[it.g] : 0)) * (D * BN);
 
-  // ---- this lane's two query columns (one per 32-row block of the wavefront)
-  bf16x8 Q[2][KK];
-  int pos[2];        // suffix position of the query (causal bound)
-  int64_t orow[2];   // packed (token, head) row of the query, -1 when past the end
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const int m = it.row0 + wave * 64 + qb * 32 + l32;
+  // ---- this lane's query column
+  bf16x8 Q[KK];
+  int pos;        // suffix position of the query (causal bound)
+  int64_t orow;   // packed (token, head) row of the query, -1 when past the end
+  {
+    const int m = it.row0 + wave * ROWS_PER_WAVE + l32;
     if (m < nrows) {
       const int i = m / group, hh = m - i * group;
-      pos[qb] = i;
-      orow[qb] = (int64_t)(off_g + i) * Hq + it.c * group + hh;
-      const __bf16* qp = q + orow[qb] * D + 8 * hf;
+      pos = i;
+      orow = (int64_t)(off_g + i) * Hq + it.c * group + hh;
+      const __bf16* qp = q + orow * D + 8 * hf;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) Q[qb][kk] = *reinterpret_cast<const bf16x8*>(qp + 16 * kk);
+      for (int kk = 0; kk < KK; ++kk) Q[kk] = *reinterpret_cast<const bf16x8*>(qp + 16 * kk);
     } else {
-      pos[qb] = 0x7fffffff;
-      orow[qb] = -1;
+      pos = 0x7fffffff;
+      orow = -1;
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) Q[qb][kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      for (int kk = 0; kk < KK; ++kk) Q[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
     }
   }
   // first suffix position among the wavefront's rows: tiles reaching past it need the mask
-  const int wave_first_pos = (it.row0 + wave * 64) / group;
+  const int wave_first_pos = (it.row0 + wave * ROWS_PER_WAVE) / group;
 
-  f32x16 O[DB][2];
+  // ---- per-lane LDS byte offsets of the operand reads (the stage base is added as an immediate)
+  int koff[KK];  // K operand (key = kb*32 + l32, channels 16kk + 8hf ..): chunk 2kk + hf
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk)
+    koff[kk] = l32 * TL::ROWB + (((2 * kk + hf) ^ swizzle_term(l32, TL::ROWB)) << 4);
+  int voff[4];   // V^T operand (channel = db*32 + l32, 16-key chunk ch): chunk 2ch + hf
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) voff[ch] = TL::KBYTES + l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
+
+  // ---- per-lane source of the direct-to-LDS K loads: lane writes LDS chunk `lane` of its block
+  constexpr int LANES_PER_ROW = TL::ROWB / 16, ROWS_PER_BLOCK = 1024 / TL::ROWB;
+  int krow[TL::KBLOCKS_PER_WAVE], kcol[TL::KBLOCKS_PER_WAVE];
+#pragma unroll
+  for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
+    const int row = (wave * TL::KBLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
+    krow[n] = row;
+    kcol[n] = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;  // logical chunk -> element offset
+  }
+
+  auto issue_loads = [&](int tile, int stage) {
+    unsigned char* st = smem + stage * TL::STAGE;
+#pragma unroll
+    for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
+      int key = tile * BN + krow[n];
+      key = key < nkeys ? key : nkeys - 1;  // rows past the end repeat the last key; their scores are masked
+      const __bf16* src = kbase + key * row_stride + kcol[n];
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src,
+                                       (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+    }
+    const __bf16* vsrc = vtbase + (int64_t)tile * (D * BN) + lane * 8;
+#pragma unroll
+    for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n) {
+      const int b = wave * TL::VBLOCKS_PER_WAVE + n;
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(vsrc + b * 512),
+                                       (LDS_PTR(void))(st + TL::KBYTES + b * 1024), 16, 0, 0);
+    }
+  };
+
+  f32x16 O[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) O[db][qb][i] = 0.f;
-  float mref[2] = {-INFINITY, -INFINITY};  // reference maximum (raw dot-product units)
-  float lsum[2] = {0.f, 0.f};              // this lane's share of the row sum
+    for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
+  float mref = -INFINITY;  // reference maximum (raw dot-product units)
+  float lsum = 0.f;        // this lane's share of the row sum
   const float c_log2 = scale * 1.4426950408889634f;
   const float rescale_raw = RESCALE_LOG2 / c_log2;
 
   const int ntiles = (nkeys + BN - 1) / BN;
-  TileRegs<D> regs;
-  load_tile<D>(regs, kbase, vbase, row_stride, 0, nkeys, tid);
-  store_tile<D>(regs, smem, tid);
+  issue_loads(0, 0);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
 
   for (int tile = 0; tile < ntiles; ++tile) {
-    unsigned char* stage = smem + (tile & 1) * Lds<D>::STAGE;
-    const bool has_next = tile + 1 < ntiles;
-    if (has_next) load_tile<D>(regs, kbase, vbase, row_stride, (tile + 1) * BN, nkeys, tid);
+    const int stage = tile & 1;
+    if (tile + 1 < ntiles) issue_loads(tile + 1, stage ^ 1);
+    const unsigned char* st = smem + stage * TL::STAGE;
 
-    // ---- S^T = K Q^T : [64 keys][64 queries] as 2x2 blocks of 32x32
-    f32x16 S[2][2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) S[kb][qb][i] = 0.f;
+    // ---- S^T = K Q^T : [64 keys][32 queries] as 2 blocks of 32x32
+    f32x16 S[2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
-      const unsigned char* krow = stage + (kb * 32 + l32) * Lds<D>::KSTRIDE + hf * 16;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) S[kb][i] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(krow + kk * 32);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) S[kb][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Q[qb][kk], S[kb][qb], 0, 0, 0);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk]);
+        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Q[kk], S[kb], 0, 0, 0);
       }
     }
 
@@ -207,106 +207,81 @@ __global__ __launch_bounds__(NTHREADS) void pass_bf16_kernel(const __bf16* __res
     const int key_tile0 = tile * BN;
     const bool need_mask = CAUSAL ? (key_tile0 + BN - 1 > wave_first_pos) : (key_tile0 + BN > nkeys);
     if (need_mask) {
+      const int limit = CAUSAL ? pos : nkeys - 1;  // last visible key
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        const int limit = CAUSAL ? pos[qb] : nkeys - 1;  // last visible key
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const int key = key_tile0 + kb * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
-            if (key > limit) S[kb][qb][i] = -INFINITY;
-          }
-      }
+        for (int i = 0; i < 16; ++i) {
+          const int key = key_tile0 + kb * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
+          if (key > limit) S[kb][i] = -INFINITY;
+        }
     }
 
     // ---- online softmax with lazy reference maximum
-    float mx[2];
+    float t = fmaxf(S[0][0], S[1][0]);
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      float t = S[0][qb][0];
+    for (int i = 1; i < 16; ++i) t = fmaxf(t, fmaxf(S[0][i], S[1][i]));
+    const float mx = pair_max(t);
+    if (__any(mx - mref > rescale_raw)) {
+      const float mnew = fmaxf(mref, mx);
+      const float alpha = __builtin_amdgcn_exp2f((mref - mnew) * c_log2);  // first tile: exp2(-inf) = 0
+      lsum *= alpha;
 #pragma unroll
-      for (int i = 1; i < 16; ++i) t = fmaxf(t, S[0][qb][i]);
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) t = fmaxf(t, S[1][qb][i]);
-      mx[qb] = pair_max(t);
+        for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
+      mref = mnew;
     }
-    const bool grow = (mx[0] - mref[0] > rescale_raw) || (mx[1] - mref[1] > rescale_raw);
-    if (__any(grow)) {
+    const float mc = mref * c_log2;
+    bf16x8 Pb[4];  // [16-key chunk]: B operand of the PV product
+    float lacc[2] = {0.f, 0.f};
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
-        const float mnew = fmaxf(mref[qb], mx[qb]);
-        const float alpha = __builtin_amdgcn_exp2f((mref[qb] - mnew) * c_log2);  // first tile: exp2(-inf) = 0
-        lsum[qb] *= alpha;
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int h2 = 0; h2 < 2; ++h2) {
+        bf16x8 b;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) O[db][qb][i] *= alpha;
-        mref[qb] = mnew;
-      }
-    }
-    bf16x8 Pb[2][4];  // [qb][16-key chunk]: B operand of the PV product
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const float mc = mref[qb] * c_log2;
-#pragma unroll
-      for (int kb = 0; kb < 2; ++kb) {
-        float pr[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          pr[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][qb][i], c_log2, -mc));
-          lsum[qb] += pr[i];
+        for (int e = 0; e < 8; e += 2) {
+          const f32x2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e], c_log2, -mc)),
+                            __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e + 1], c_log2, -mc))};
+          const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+          lacc[(e >> 1) & 1] += pr[0] + pr[1];
+          b[e] = pk[0];
+          b[e + 1] = pk[1];
         }
-#pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          bf16x8 b;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) b[e] = (__bf16)pr[8 * h2 + e];
-          Pb[qb][kb * 2 + h2] = b;
-        }
+        Pb[kb * 2 + h2] = b;
       }
-    }
+    lsum += lacc[0] + lacc[1];
 
     // ---- O^T += V^T P^T.  Chunk ch covers keys 16*ch .. 16*ch+15 of the tile; slot e of lane
     //      half hf is key 16*ch + 4*hf + e (e < 4) or 16*ch + 8 + 4*hf + (e - 4), the order in
-    //      which the score accumulator delivered the probabilities.
-    const unsigned char* vst = stage + Lds<D>::KBYTES;
-    const int vkey = 4 * hf + ((lane & 15) >> 2);
-    const int vcol = (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
+    //      which the score accumulator delivered the probabilities (and the V^T image stores).
 #pragma unroll
-    for (int ch = 0; ch < 4; ++ch) {
+    for (int ch = 0; ch < 4; ++ch)
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
-        const unsigned char* p0 = vst + (16 * ch + vkey) * Lds<D>::VSTRIDE + db * 64 + vcol;
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))p0);
-        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((LDS_PTR(s16x4))(p0 + 8 * Lds<D>::VSTRIDE));
-        const s16x8 a16 = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        const bf16x8 a = __builtin_bit_cast(bf16x8, a16);
-#pragma unroll
-        for (int qb = 0; qb < 2; ++qb) O[db][qb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[qb][ch], O[db][qb], 0, 0, 0);
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[ch]);
+        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[ch], O[db], 0, 0, 0);
       }
-    }
 
-    if (has_next) store_tile<D>(regs, smem + ((tile + 1) & 1) * Lds<D>::STAGE, tid);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // next tile has landed in the other stage
     __syncthreads();
   }
 
   // ---- epilogue: normalise and write the partial.  Register i of block db is channel
   //      db*32 + 8*(i/4) + 4*hf + i%4 of this lane's query.
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    const float l = pair_sum(lsum[qb]);
-    if (orow[qb] < 0) continue;
+  const float l = pair_sum(lsum);
+  if (orow >= 0) {
     const float inv = 1.0f / l;
-    float* op = o_part + orow[qb] * D + 4 * hf;
+    float* op = o_part + orow * D + 4 * hf;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        f32x4 w = {O[db][qb][4 * a] * inv, O[db][qb][4 * a + 1] * inv, O[db][qb][4 * a + 2] * inv, O[db][qb][4 * a + 3] * inv};
+        f32x4 w = {O[db][4 * a] * inv, O[db][4 * a + 1] * inv, O[db][4 * a + 2] * inv, O[db][4 * a + 3] * inv};
         *reinterpret_cast<f32x4*>(op + db * 32 + 8 * a) = w;
       }
-    if (hf == 0) lse_part[orow[qb]] = mref[qb] * scale + __logf(l);
+    if (hf == 0) lse_part[orow] = mref * scale + __logf(l);
   }
 }
 
@@ -317,10 +292,11 @@ int launch_pass_bf16(const PassArgs& a, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   const __bf16* q = static_cast<const __bf16*>(a.q);
   const __bf16* k = static_cast<const __bf16*>(a.k);
-  const __bf16* v = static_cast<const __bf16*>(a.v);
+  const __bf16* vt = static_cast<const __bf16*>(a.vt);
   const unsigned grid = (unsigned)a.num_items;
-#define PA_LAUNCH(DD, CC) \
-  pass_bf16_kernel<DD, CC><<<grid, NTHREADS, 0, s>>>(q, k, v, a.o_part, a.lse_part, a.items, a.cu, a.Hq, a.Hkv, a.group, a.scale)
+#define PA_LAUNCH(DD, CC)                                                                                         \
+  pass_bf16_kernel<DD, CC><<<grid, NTHREADS, 0, s>>>(q, k, vt, a.o_part, a.lse_part, a.items, a.cu, a.vt_off, \
+                                                     a.vt_tiles_per_head, a.Hq, a.Hkv, a.group, a.scale)
   if (a.D == 128) {
     if (a.causal) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
   } else {

@@ -12,7 +12,7 @@ namespace pa {
 
 // Tile geometry of the two attention passes: one work item = ROWS_PER_ITEM stacked query
 // rows of one (kv head, rollout); keys are swept in LDS tiles of KEYS_PER_TILE.
-constexpr int ROWS_PER_ITEM = 256;
+constexpr int ROWS_PER_ITEM = 128;
 constexpr int KEYS_PER_TILE = 64;
 constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
 
@@ -33,6 +33,9 @@ struct PassArgs {
   float* lse_part;      // [T, Hq]    fp32, natural-log LSE of the partial
   const WorkItem* items;
   const int32_t* cu;    // [G+1] packed-row offsets of the rollouts
+  const void* vt;       // bf16 path: transposed-V tile images of this pass (see vt_image.hip)
+  const int32_t* vt_off;  // [G+1] first tile image of each rollout (suffix pass); null for the prefix pass
+  int64_t vt_tiles_per_head;  // tile images per kv head in `vt`
   int64_t num_items;
   int32_t Hq, Hkv, D, group;
   float scale;          // softmax scale
@@ -55,6 +58,18 @@ struct MergeArgs {
 // Launchers; each returns a hipError_t value as int (0 = success).  `stream` is a hipStream_t.
 int launch_pass_bf16(const PassArgs& a, void* stream);
 int launch_pass_f32(const PassArgs& a, void* stream);
+// Builds the transposed-V tile images of both passes for the bf16 path.
+struct VtArgs {
+  const void* v_prefix;   // [P, Hkv, D] bf16 (may be null when P == 0)
+  const void* v_suffix;   // [T, Hkv, D] bf16
+  void* vt_prefix;        // [Hkv][tiles_prefix][D][64] bf16 images
+  void* vt_suffix;        // [Hkv][tiles_suffix][D][64] bf16 images
+  const int32_t* cu;      // [G+1]
+  const int32_t* vt_off;  // [G+1]
+  int64_t P;
+  int32_t tiles_prefix, tiles_suffix, G, Hkv, D;
+};
+int launch_vt_images(const VtArgs& a, void* stream);
 int launch_merge(const MergeArgs& a, void* stream);
 int launch_lse_export(const float* lse_th, float* lse_ht, int64_t T, int32_t Hq, void* stream);
 
@@ -64,12 +79,15 @@ struct prefix_attn_plan {
   prefix_attn_desc_t desc;             // suffix_lens points into `lens`
   std::vector<int32_t> lens;           // [G]
   std::vector<int32_t> cu;             // [G+1]
+  std::vector<int32_t> vt_off;         // [G+1] tile-image offsets of the rollouts (KEYS_PER_TILE keys per image)
   int64_t T = 0;
   int32_t group = 1;                   // Hq / Hkv
   std::vector<pa::WorkItem> items[2];  // 0 = prefix pass, 1 = suffix pass
   // device-side copies (null for a host-only plan)
-  int32_t* d_cu = nullptr;
+  int32_t* d_cu = nullptr;             // cu followed by vt_off, one allocation
+  int32_t* d_vt_off = nullptr;
+  int32_t tiles_prefix = 0, tiles_suffix = 0;
   pa::WorkItem* d_items[2] = {nullptr, nullptr};
   // workspace layout, byte offsets
-  size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, ws_bytes = 0;
+  size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;
 };

@@ -104,6 +104,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     p->cu.assign(desc->num_rollouts + 1, 0);
     for (int g = 0; g < desc->num_rollouts; ++g) p->cu[g + 1] = p->cu[g] + p->lens[g];
     p->T = p->cu.back();
+    p->vt_off.assign(desc->num_rollouts + 1, 0);
+    for (int g = 0; g < desc->num_rollouts; ++g)
+      p->vt_off[g + 1] = p->vt_off[g] + (p->lens[g] + pa::KEYS_PER_TILE - 1) / pa::KEYS_PER_TILE;
+    p->tiles_suffix = p->vt_off.back();
+    p->tiles_prefix = (int32_t)((desc->prefix_len + pa::KEYS_PER_TILE - 1) / pa::KEYS_PER_TILE);
     p->group = desc->num_q_heads / desc->num_kv_heads;
     build_prefix_items(*p);
     build_suffix_items(*p);
@@ -119,14 +124,24 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
   p->off_lse1 = 2 * o_bytes;
   p->off_lse2 = p->off_lse1 + l_bytes;
   p->off_lse = p->off_lse2 + l_bytes;
-  p->ws_bytes = p->off_lse + l_bytes;
+  p->off_vtp = p->off_lse + l_bytes;
+  size_t end = p->off_vtp;
+  if (desc->dtype == PA_BF16) {  // transposed-V tile images, bf16 path only
+    const size_t image = (size_t)desc->head_dim * pa::KEYS_PER_TILE * 2;
+    p->off_vts = p->off_vtp + align_up((size_t)desc->num_kv_heads * p->tiles_prefix * image, 256);
+    end = p->off_vts + align_up((size_t)desc->num_kv_heads * p->tiles_suffix * image, 256);
+  }
+  p->ws_bytes = end;
 
   if (desc->device >= 0) {
     int prev = 0;
     bool ok = hipGetDevice(&prev) == hipSuccess && hipSetDevice(desc->device) == hipSuccess;
     if (ok) {
-      ok = hipMalloc((void**)&p->d_cu, p->cu.size() * sizeof(int32_t)) == hipSuccess &&
-           hipMemcpy(p->d_cu, p->cu.data(), p->cu.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+      const size_t n = p->cu.size();
+      ok = hipMalloc((void**)&p->d_cu, 2 * n * sizeof(int32_t)) == hipSuccess &&
+           hipMemcpy(p->d_cu, p->cu.data(), n * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess &&
+           hipMemcpy(p->d_cu + n, p->vt_off.data(), n * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+      p->d_vt_off = p->d_cu + n;
       for (int s = 0; ok && s < 2; ++s) {
         if (p->items[s].empty()) continue;
         const size_t bytes = p->items[s].size() * sizeof(WorkItem);

@@ -81,7 +81,10 @@ def test_workspace_size_matches_layout():
     T, Hq, D = 1152 * 8, 28, 128
     assert plan.total_tokens == T
     need = 2 * T * Hq * D * 4 + 3 * T * Hq * 4
-    assert need <= plan.workspace_bytes <= need + 5 * 256
+    images = 4 * (4096 // 64 + 8 * (1152 // 64)) * D * 64 * 2     # bf16: transposed-V tile images
+    assert need + images <= plan.workspace_bytes <= need + images + 7 * 256
+    f32 = host_plan(dtype="f32")
+    assert need <= f32.workspace_bytes <= need + 5 * 256
 
 
 def coverage(plan, Hq, Hkv, P, lens):
