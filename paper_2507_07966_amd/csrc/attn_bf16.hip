@@ -20,12 +20,14 @@
 //     accumulator then holds, per lane, 16 keys of ONE query column, so the row maximum is
 //     in-register plus one exchange between lane l and lane l+32, and the probabilities are
 //     already laid out as the B operand of O^T += V^T P^T.
-//   - Online softmax with a lazily updated reference maximum: the accumulators are rescaled
-//     only when some row's maximum exceeds the reference by more than 2^8, which keeps every
-//     probability below 2^8 (harmless in fp32/bf16) and removes almost all rescaling work.
+//   - Online softmax with a lazily updated reference maximum: the reference moves (and the
+//     accumulators are rescaled) only when a tile's probabilities leave a safe range, which
+//     is detected from the tile's row sum; the common tile needs no maximum search at all.
 //     The row sum is accumulated in fp32 from the unrounded probabilities, which keeps the
 //     LSE error at fp32 level even for rows that see only a few keys.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "common.h"
 
@@ -46,7 +48,10 @@ constexpr int BN = KEYS_PER_TILE;  // keys per LDS tile
 constexpr int NTHREADS = 256;
 constexpr int ROWS_PER_WAVE = ROWS_PER_ITEM / 4;
 static_assert(ROWS_PER_WAVE == 32, "one 32-column MFMA block of queries per wavefront");
-constexpr float RESCALE_LOG2 = 8.0f;  // lazy-rescale threshold in log2 units
+// A tile's probabilities are accepted without a maximum search while each lane's partial row
+// sum of the tile stays below SAFE_SUM; every probability is then below 2^16, far inside the
+// fp32/bf16 range, and the running sums cannot overflow (2^16 * 2^30 keys < 2^127).
+constexpr float SAFE_SUM = 65536.0f;
 
 // LDS stage: K tile [64 keys][D] (rows of D*2 bytes) followed by the V^T image [D][64 slots]
 // (rows of 128 bytes).  16-byte chunk j of a row r is stored at chunk position
@@ -141,33 +146,47 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
 #pragma unroll
   for (int ch = 0; ch < 4; ++ch) voff[ch] = TL::KBYTES + l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
 
-  // ---- per-lane source of the direct-to-LDS K loads: lane writes LDS chunk `lane` of its block
+  // ---- per-lane source of the direct-to-LDS K loads: lane writes LDS chunk `lane` of its block.
+  //      The pointer of tile 0 is kept per load; a tile advances it by a uniform stride.
   constexpr int LANES_PER_ROW = TL::ROWB / 16, ROWS_PER_BLOCK = 1024 / TL::ROWB;
   int krow[TL::KBLOCKS_PER_WAVE], kcol[TL::KBLOCKS_PER_WAVE];
+  const __bf16* ksrc[TL::KBLOCKS_PER_WAVE];
 #pragma unroll
   for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
     const int row = (wave * TL::KBLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
     krow[n] = row;
     kcol[n] = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;  // logical chunk -> element offset
+    ksrc[n] = kbase + row * row_stride + kcol[n];
   }
+  const __bf16* vsrc0 = vtbase + (wave * TL::VBLOCKS_PER_WAVE) * 512 + lane * 8;
+  const int64_t ktile_stride = (int64_t)BN * row_stride;  // elements per tile of K
+  const int ntiles = (nkeys + BN - 1) / BN;
+  const int full_tiles = nkeys / BN;  // tiles whose 64 keys all exist
 
-  auto issue_loads = [&](int tile, int stage) {
-    unsigned char* st = smem + stage * TL::STAGE;
+  auto issue_loads = [&](int tile, auto stage_c) {
+    constexpr int STAGE_OFF = decltype(stage_c)::value * TL::STAGE;
+    unsigned char* st = smem + STAGE_OFF;
+    if (tile < full_tiles) {
+      const int64_t adv = tile * ktile_stride;  // uniform
 #pragma unroll
-    for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
-      int key = tile * BN + krow[n];
-      key = key < nkeys ? key : nkeys - 1;  // rows past the end repeat the last key; their scores are masked
-      const __bf16* src = kbase + key * row_stride + kcol[n];
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))src,
-                                       (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
-    }
-    const __bf16* vsrc = vtbase + (int64_t)tile * (D * BN) + lane * 8;
+      for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n)
+        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(ksrc[n] + adv),
+                                         (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+    } else {  // last, partial tile: rows past the end repeat the last key; their scores are masked
 #pragma unroll
-    for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n) {
-      const int b = wave * TL::VBLOCKS_PER_WAVE + n;
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(vsrc + b * 512),
-                                       (LDS_PTR(void))(st + TL::KBYTES + b * 1024), 16, 0, 0);
+      for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
+        int key = tile * BN + krow[n];
+        key = key < nkeys ? key : nkeys - 1;
+        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(kbase + key * row_stride + kcol[n]),
+                                         (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+      }
     }
+    const __bf16* vsrc = vsrc0 + (int64_t)tile * (D * BN);
+#pragma unroll
+    for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n)
+      __builtin_amdgcn_global_load_lds(
+          (GLB_PTR(const void))(vsrc + n * 512),
+          (LDS_PTR(void))(st + TL::KBYTES + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
   };
 
   f32x16 O[DB];
@@ -178,30 +197,45 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
   float mref = -INFINITY;  // reference maximum (raw dot-product units)
   float lsum = 0.f;        // this lane's share of the row sum
   const float c_log2 = scale * 1.4426950408889634f;
-  const float rescale_raw = RESCALE_LOG2 / c_log2;
 
-  const int ntiles = (nkeys + BN - 1) / BN;
-  issue_loads(0, 0);
-  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-  __syncthreads();
+  // One tile: scores, online softmax against the reference maximum, PV.  STAGE is a
+  // compile-time constant so every LDS address is base register + immediate.
+  auto compute_tile = [&](int tile, auto stage_c) {
+    constexpr int STAGE_OFF = decltype(stage_c)::value * TL::STAGE;
+    const unsigned char* st = smem + STAGE_OFF;
 
-  for (int tile = 0; tile < ntiles; ++tile) {
-    const int stage = tile & 1;
-    if (tile + 1 < ntiles) issue_loads(tile + 1, stage ^ 1);
-    const unsigned char* st = smem + stage * TL::STAGE;
-
-    // ---- S^T = K Q^T : [64 keys][32 queries] as 2 blocks of 32x32
+    // ---- S^T = K Q^T : [64 keys][32 queries] as 2 blocks of 32x32.  Operand reads run
+    //      PF contraction steps ahead of the MFMAs that consume them.
     f32x16 S[2];
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb) {
+    for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[kb][i] = 0.f;
+    {
+      constexpr int PF = 3;
+      bf16x8 ka[KK][2];
+#pragma unroll
+      for (int kk = 0; kk < PF && kk < KK; ++kk)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) ka[kk][kb] = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk]);
+      __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead: the scheduler must not sink them to their uses
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk]);
-        S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Q[kk], S[kb], 0, 0, 0);
+        if (kk + PF < KK) {
+#pragma unroll
+          for (int kb = 0; kb < 2; ++kb)
+            ka[kk + PF][kb] = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk + PF]);
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][kb], Q[kk], S[kb], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
+    // V^T operands of the first PV chunk are fetched now so that their latency hides behind the softmax
+    bf16x8 va0[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) va0[db] = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[0]);
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- mask: register i of block kb holds key tile*64 + kb*32 + 8*(i/4) + 4*hf + i%4
     const int key_tile0 = tile * BN;
@@ -217,13 +251,45 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
         }
     }
 
-    // ---- online softmax with lazy reference maximum
-    float t = fmaxf(S[0][0], S[1][0]);
+    // ---- online softmax against a lazily updated reference maximum.
+    // Fast path: p = exp2(c*s - c*mref) with no maximum search at all; the tile's row sum
+    // (needed anyway) tells whether any p left the safe range.  Slow path (first tile, or a
+    // row whose scores outgrew the reference so far that the sum check fails): find the maximum,
+    // move the reference, rescale the accumulators, and recompute p.
+    bf16x8 Pb[4];  // [16-key chunk]: B operand of the PV product
+    float lacc[2];
+    auto probabilities = [&]() {
+      const float mc = mref * c_log2;
+      lacc[0] = 0.f;
+      lacc[1] = 0.f;
 #pragma unroll
-    for (int i = 1; i < 16; ++i) t = fmaxf(t, fmaxf(S[0][i], S[1][i]));
-    const float mx = pair_max(t);
-    if (__any(mx - mref > rescale_raw)) {
-      const float mnew = fmaxf(mref, mx);
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int h2 = 0; h2 < 2; ++h2) {
+          bf16x8 b;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2) {
+            const f32x2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e], c_log2, -mc)),
+                              __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e + 1], c_log2, -mc))};
+            const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+            lacc[(e >> 1) & 1] += pr[0] + pr[1];
+            b[e] = pk[0];
+            b[e + 1] = pk[1];
+          }
+          Pb[kb * 2 + h2] = b;
+        }
+    };
+    bool redo = (mref == -INFINITY);
+    if (!__any(redo)) {
+      probabilities();
+      // each p <= this lane's partial sum; !(x <= bound) is also true for NaN (inf - inf)
+      redo = !(lacc[0] + lacc[1] <= SAFE_SUM);
+    }
+    if (__any(redo)) {
+      float t = fmaxf(S[0][0], S[1][0]);
+#pragma unroll
+      for (int i = 1; i < 16; ++i) t = fmaxf(t, fmaxf(S[0][i], S[1][i]));
+      const float mnew = fmaxf(mref, pair_max(t));
       const float alpha = __builtin_amdgcn_exp2f((mref - mnew) * c_log2);  // first tile: exp2(-inf) = 0
       lsum *= alpha;
 #pragma unroll
@@ -231,40 +297,45 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
       mref = mnew;
+      probabilities();
     }
-    const float mc = mref * c_log2;
-    bf16x8 Pb[4];  // [16-key chunk]: B operand of the PV product
-    float lacc[2] = {0.f, 0.f};
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2) {
-        bf16x8 b;
-#pragma unroll
-        for (int e = 0; e < 8; e += 2) {
-          const f32x2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e], c_log2, -mc)),
-                            __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e + 1], c_log2, -mc))};
-          const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
-          lacc[(e >> 1) & 1] += pr[0] + pr[1];
-          b[e] = pk[0];
-          b[e + 1] = pk[1];
-        }
-        Pb[kb * 2 + h2] = b;
-      }
     lsum += lacc[0] + lacc[1];
 
     // ---- O^T += V^T P^T.  Chunk ch covers keys 16*ch .. 16*ch+15 of the tile; slot e of lane
     //      half hf is key 16*ch + 4*hf + e (e < 4) or 16*ch + 8 + 4*hf + (e - 4), the order in
     //      which the score accumulator delivered the probabilities (and the V^T image stores).
+    {
+      bf16x8 va[2][DB];
 #pragma unroll
-    for (int ch = 0; ch < 4; ++ch)
+      for (int db = 0; db < DB; ++db) va[0][db] = va0[db];
 #pragma unroll
-      for (int db = 0; db < DB; ++db) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[ch]);
-        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Pb[ch], O[db], 0, 0, 0);
+      for (int ch = 0; ch < 4; ++ch) {
+        if (ch + 1 < 4) {
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+            va[(ch + 1) & 1][db] = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[ch + 1]);
+        }
+#pragma unroll
+        for (int db = 0; db < DB; ++db) O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ch & 1][db], Pb[ch], O[db], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
       }
+    }
+  };
 
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // next tile has landed in the other stage
+  using Stage0 = std::integral_constant<int, 0>;
+  using Stage1 = std::integral_constant<int, 1>;
+  issue_loads(0, Stage0{});
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+  __syncthreads();
+  for (int tile = 0; tile < ntiles; tile += 2) {
+    if (tile + 1 < ntiles) issue_loads(tile + 1, Stage1{});
+    compute_tile(tile, Stage0{});
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // the next tile has landed in the other stage
+    __syncthreads();
+    if (tile + 1 >= ntiles) break;
+    if (tile + 2 < ntiles) issue_loads(tile + 2, Stage0{});
+    compute_tile(tile + 1, Stage1{});
+    __builtin_amdgcn_s_waitcnt(0x0F70);
     __syncthreads();
   }
 
