@@ -20,6 +20,8 @@
 //     accumulator then holds, per lane, 16 keys of ONE query column, so the row maximum is
 //     in-register plus one exchange between lane l and lane l+32, and the probabilities are
 //     already laid out as the B operand of O^T += V^T P^T.
+//   - Software pipeline inside a wavefront: the MFMAs that compute the scores of tile t+1 are
+//     interleaved with the VALU softmax of tile t, so both pipes work at once.
 //   - Online softmax with a lazily updated reference maximum: the reference moves (and the
 //     accumulators are rescaled) only when a tile's probabilities leave a safe range, which
 //     is detected from the tile's row sum; the common tile needs no maximum search at all.
@@ -53,8 +55,8 @@ static_assert(ROWS_PER_WAVE == 32, "one 32-column MFMA block of queries per wave
 // fp32/bf16 range, and the running sums cannot overflow (2^16 * 2^30 keys < 2^127).
 constexpr float SAFE_SUM = 65536.0f;
 
-// LDS stage: K tile [64 keys][D] (rows of D*2 bytes) followed by the V^T image [D][64 slots]
-// (rows of 128 bytes).  16-byte chunk j of a row r is stored at chunk position
+// LDS buffers: K tile [64 keys][D] (rows of D*2 bytes) and V^T image [D][64 slots] (rows of
+// 128 bytes), two of each.  16-byte chunk j of a row r is stored at chunk position
 //   j ^ (r & 15)          for 256-byte rows,
 //   j ^ ((r >> 1) & 7)    for 128-byte rows,
 // so that 16 consecutive rows read at the same logical chunk cover all 64 banks.
@@ -137,14 +139,16 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
   // first suffix position among the wavefront's rows: tiles reaching past it need the mask
   const int wave_first_pos = (it.row0 + wave * ROWS_PER_WAVE) / group;
 
-  // ---- per-lane LDS byte offsets of the operand reads (the stage base is added as an immediate)
+  // ---- LDS: two K buffers then two V^T buffers.  Per-lane byte offsets of the operand reads
+  //      inside a buffer (the buffer base is an immediate).
+  constexpr int KBUF0 = 0, VBUF0 = 2 * TL::KBYTES;
   int koff[KK];  // K operand (key = kb*32 + l32, channels 16kk + 8hf ..): chunk 2kk + hf
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk)
     koff[kk] = l32 * TL::ROWB + (((2 * kk + hf) ^ swizzle_term(l32, TL::ROWB)) << 4);
   int voff[4];   // V^T operand (channel = db*32 + l32, 16-key chunk ch): chunk 2ch + hf
 #pragma unroll
-  for (int ch = 0; ch < 4; ++ch) voff[ch] = TL::KBYTES + l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
+  for (int ch = 0; ch < 4; ++ch) voff[ch] = l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
 
   // ---- per-lane source of the direct-to-LDS K loads: lane writes LDS chunk `lane` of its block.
   //      The pointer of tile 0 is kept per load; a tile advances it by a uniform stride.
@@ -163,30 +167,31 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
   const int ntiles = (nkeys + BN - 1) / BN;
   const int full_tiles = nkeys / BN;  // tiles whose 64 keys all exist
 
-  auto issue_loads = [&](int tile, auto stage_c) {
-    constexpr int STAGE_OFF = decltype(stage_c)::value * TL::STAGE;
-    unsigned char* st = smem + STAGE_OFF;
+  auto issue_k = [&](int tile, auto buf_c) {  // K tile -> K buffer buf
+    unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
     if (tile < full_tiles) {
       const int64_t adv = tile * ktile_stride;  // uniform
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n)
         __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(ksrc[n] + adv),
-                                         (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+                                         (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
     } else {  // last, partial tile: rows past the end repeat the last key; their scores are masked
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
         int key = tile * BN + krow[n];
         key = key < nkeys ? key : nkeys - 1;
         __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(kbase + key * row_stride + kcol[n]),
-                                         (LDS_PTR(void))(st + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+                                         (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
       }
     }
+  };
+  auto issue_v = [&](int tile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
+    unsigned char* dst = smem + VBUF0 + decltype(buf_c)::value * TL::VBYTES;
     const __bf16* vsrc = vsrc0 + (int64_t)tile * (D * BN);
 #pragma unroll
     for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n)
-      __builtin_amdgcn_global_load_lds(
-          (GLB_PTR(const void))(vsrc + n * 512),
-          (LDS_PTR(void))(st + TL::KBYTES + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(vsrc + n * 512),
+                                       (LDS_PTR(void))(dst + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
   };
 
   f32x16 O[DB];
@@ -194,50 +199,21 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int i = 0; i < 16; ++i) O[db][i] = 0.f;
-  float mref = -INFINITY;  // reference maximum (raw dot-product units)
-  float lsum = 0.f;        // this lane's share of the row sum
+  float mref;        // reference maximum (raw dot-product units)
+  float lsum = 0.f;  // this lane's share of the row sum
   const float c_log2 = scale * 1.4426950408889634f;
 
-  // One tile: scores, online softmax against the reference maximum, PV.  STAGE is a
-  // compile-time constant so every LDS address is base register + immediate.
-  auto compute_tile = [&](int tile, auto stage_c) {
-    constexpr int STAGE_OFF = decltype(stage_c)::value * TL::STAGE;
-    const unsigned char* st = smem + STAGE_OFF;
-
-    // ---- S^T = K Q^T : [64 keys][32 queries] as 2 blocks of 32x32.  Operand reads run
-    //      PF contraction steps ahead of the MFMAs that consume them.
-    f32x16 S[2];
+  auto zero = [](f32x16 (&S)[2]) {
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
       for (int i = 0; i < 16; ++i) S[kb][i] = 0.f;
-    {
-      constexpr int PF = 3;
-      bf16x8 ka[KK][2];
-#pragma unroll
-      for (int kk = 0; kk < PF && kk < KK; ++kk)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) ka[kk][kb] = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk]);
-      __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead: the scheduler must not sink them to their uses
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        if (kk + PF < KK) {
-#pragma unroll
-          for (int kb = 0; kb < 2; ++kb)
-            ka[kk + PF][kb] = *reinterpret_cast<const bf16x8*>(st + kb * 32 * TL::ROWB + koff[kk + PF]);
-        }
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][kb], Q[kk], S[kb], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-    }
-    // V^T operands of the first PV chunk are fetched now so that their latency hides behind the softmax
-    bf16x8 va0[DB];
-#pragma unroll
-    for (int db = 0; db < DB; ++db) va0[db] = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[0]);
-    __builtin_amdgcn_sched_barrier(0);
-
-    // ---- mask: register i of block kb holds key tile*64 + kb*32 + 8*(i/4) + 4*hf + i%4
+  };
+  auto k_operand = [&](const unsigned char* kbuf, int kb, int kk) {
+    return *reinterpret_cast<const bf16x8*>(kbuf + kb * 32 * TL::ROWB + koff[kk]);
+  };
+  // register i of block kb holds key tile*64 + kb*32 + 8*(i/4) + 4*hf + i%4
+  auto mask_scores = [&](f32x16 (&S)[2], int tile) {
     const int key_tile0 = tile * BN;
     const bool need_mask = CAUSAL ? (key_tile0 + BN - 1 > wave_first_pos) : (key_tile0 + BN > nkeys);
     if (need_mask) {
@@ -250,93 +226,152 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
           if (key > limit) S[kb][i] = -INFINITY;
         }
     }
-
-    // ---- online softmax against a lazily updated reference maximum.
-    // Fast path: p = exp2(c*s - c*mref) with no maximum search at all; the tile's row sum
-    // (needed anyway) tells whether any p left the safe range.  Slow path (first tile, or a
-    // row whose scores outgrew the reference so far that the sum check fails): find the maximum,
-    // move the reference, rescale the accumulators, and recompute p.
-    bf16x8 Pb[4];  // [16-key chunk]: B operand of the PV product
-    float lacc[2];
-    auto probabilities = [&]() {
-      const float mc = mref * c_log2;
-      lacc[0] = 0.f;
-      lacc[1] = 0.f;
+  };
+  auto row_max = [&](const f32x16 (&S)[2]) {
+    float t = fmaxf(S[0][0], S[1][0]);
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int i = 1; i < 16; ++i) t = fmaxf(t, fmaxf(S[0][i], S[1][i]));
+    return pair_max(t);
+  };
+  // probabilities of score registers [4*j, 4*j+4) of the 32 this lane holds: p = exp2(c*s - c*mref)
+  auto prob_slice = [&](const f32x16 (&S)[2], int j, float mc, bf16x8 (&Pb)[4], float (&lacc)[2]) {
+    const int kb = j >> 2, r0 = (j & 3) * 4;
 #pragma unroll
-        for (int h2 = 0; h2 < 2; ++h2) {
-          bf16x8 b;
-#pragma unroll
-          for (int e = 0; e < 8; e += 2) {
-            const f32x2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e], c_log2, -mc)),
-                              __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][8 * h2 + e + 1], c_log2, -mc))};
-            const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
-            lacc[(e >> 1) & 1] += pr[0] + pr[1];
-            b[e] = pk[0];
-            b[e + 1] = pk[1];
-          }
-          Pb[kb * 2 + h2] = b;
-        }
-    };
-    bool redo = (mref == -INFINITY);
-    if (!__any(redo)) {
-      probabilities();
-      // each p <= this lane's partial sum; !(x <= bound) is also true for NaN (inf - inf)
-      redo = !(lacc[0] + lacc[1] <= SAFE_SUM);
+    for (int e = 0; e < 4; e += 2) {
+      const f32x2 pr = {__builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][r0 + e], c_log2, -mc)),
+                        __builtin_amdgcn_exp2f(__builtin_fmaf(S[kb][r0 + e + 1], c_log2, -mc))};
+      const bf16x2 pk = __builtin_convertvector(pr, bf16x2);
+      lacc[(e >> 1) & 1] += pr[0] + pr[1];
+      Pb[kb * 2 + (r0 >> 3)][(r0 & 7) + e] = pk[0];
+      Pb[kb * 2 + (r0 >> 3)][(r0 & 7) + e + 1] = pk[1];
     }
-    if (__any(redo)) {
-      float t = fmaxf(S[0][0], S[1][0]);
+  };
+
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
+
+  f32x16 S[2];    // scores of the tile being soft-maxed
+  bf16x8 Pb[4];   // probabilities of the previous tile, [16-key chunk]: B operand of the PV product
+  auto scores = [&](const unsigned char* kbuf) {  // S^T = K Q^T, operand reads PF steps ahead of the MFMAs
+    zero(S);
+    constexpr int PF = 2;
+    bf16x8 ka[KK][2];
 #pragma unroll
-      for (int i = 1; i < 16; ++i) t = fmaxf(t, fmaxf(S[0][i], S[1][i]));
-      const float mnew = fmaxf(mref, pair_max(t));
-      const float alpha = __builtin_amdgcn_exp2f((mref - mnew) * c_log2);  // first tile: exp2(-inf) = 0
+    for (int kk = 0; kk < PF; ++kk)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) ka[kk][kb] = k_operand(kbuf, kb, kk);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      if (kk + PF < KK) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) ka[kk + PF][kb] = k_operand(kbuf, kb, kk + PF);
+      }
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb) S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][kb], Q[kk], S[kb], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  };
+  // Online softmax against a lazily updated reference maximum: p = exp2(c*s - c*mref) is taken
+  // with no maximum search; the tile's row sum (needed anyway) tells whether any p left the
+  // safe range, and only then the maximum is searched, the reference moved, the accumulators
+  // rescaled and the probabilities recomputed.
+  auto finish_softmax = [&](bf16x8 (&Pn)[4], float (&lacc)[2]) {
+    // each p <= this lane's partial sum; !(x <= bound) is also true for NaN
+    if (__any(!(lacc[0] + lacc[1] <= SAFE_SUM))) {
+      const float mnew = fmaxf(mref, row_max(S));
+      const float alpha = __builtin_amdgcn_exp2f((mref - mnew) * c_log2);
       lsum *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) O[db][i] *= alpha;
       mref = mnew;
-      probabilities();
+      lacc[0] = 0.f;
+      lacc[1] = 0.f;
+      const float mc2 = mref * c_log2;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) prob_slice(S, j, mc2, Pn, lacc);
     }
     lsum += lacc[0] + lacc[1];
-
-    // ---- O^T += V^T P^T.  Chunk ch covers keys 16*ch .. 16*ch+15 of the tile; slot e of lane
-    //      half hf is key 16*ch + 4*hf + e (e < 4) or 16*ch + 8 + 4*hf + (e - 4), the order in
-    //      which the score accumulator delivered the probabilities (and the V^T image stores).
-    {
-      bf16x8 va[2][DB];
 #pragma unroll
-      for (int db = 0; db < DB; ++db) va[0][db] = va0[db];
+    for (int ch = 0; ch < 4; ++ch) Pb[ch] = Pn[ch];
+  };
+  // O^T += V^T P^T for the tile whose probabilities are in Pb.  Chunk ch covers keys
+  // 16*ch .. 16*ch+15 of the tile; slot e of lane half hf is key 16*ch + 4*hf + e (e < 4) or
+  // 16*ch + 8 + 4*hf + (e - 4), the order in which the score accumulator delivered the
+  // probabilities (and the V^T image stores).  With OVERLAP the softmax of the next tile
+  // (scores in S) is interleaved, two 4-score slices per chunk, so the VALU works while the
+  // MFMA pipe does; each V^T operand register is refilled right after the MFMA that read it.
+  auto pv = [&](const unsigned char* vbuf, auto overlap_c, bf16x8 (&Pn)[4], float (&lacc)[2]) {
+    constexpr bool OVERLAP = decltype(overlap_c)::value;
+    const float mc = mref * c_log2;
+    bf16x8 va[DB];
 #pragma unroll
-      for (int ch = 0; ch < 4; ++ch) {
-        if (ch + 1 < 4) {
+    for (int db = 0; db < DB; ++db) va[db] = *reinterpret_cast<const bf16x8*>(vbuf + db * 32 * 128 + voff[0]);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int db = 0; db < DB; ++db)
-            va[(ch + 1) & 1][db] = *reinterpret_cast<const bf16x8*>(st + db * 32 * 128 + voff[ch + 1]);
-        }
+    for (int ch = 0; ch < 4; ++ch) {
 #pragma unroll
-        for (int db = 0; db < DB; ++db) O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[ch & 1][db], Pb[ch], O[db], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
+      for (int db = 0; db < DB; ++db) {
+        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[db], Pb[ch], O[db], 0, 0, 0);
+        if (ch + 1 < 4) va[db] = *reinterpret_cast<const bf16x8*>(vbuf + db * 32 * 128 + voff[ch + 1]);
       }
+      if (OVERLAP) {
+        prob_slice(S, 2 * ch, mc, Pn, lacc);
+        prob_slice(S, 2 * ch + 1, mc, Pn, lacc);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // keep this MFMA / VALU interleave
     }
   };
 
-  using Stage0 = std::integral_constant<int, 0>;
-  using Stage1 = std::integral_constant<int, 1>;
-  issue_loads(0, Stage0{});
+  // ---- prologue: tiles 0 (and K of tile 1) in flight; scores and softmax of tile 0
+  issue_k(0, B0{});
+  issue_v(0, B0{});
+  if (ntiles > 1) issue_k(1, B1{});
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
-  for (int tile = 0; tile < ntiles; tile += 2) {
-    if (tile + 1 < ntiles) issue_loads(tile + 1, Stage1{});
-    compute_tile(tile, Stage0{});
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // the next tile has landed in the other stage
+  scores(smem + KBUF0);
+  mask_scores(S, 0);
+  mref = row_max(S);  // finite: key 0 is visible to every row
+  {
+    bf16x8 Pn[4];
+    float lacc[2] = {0.f, 0.f};
+    const float mc = mref * c_log2;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) prob_slice(S, j, mc, Pn, lacc);
+    finish_softmax(Pn, lacc);
+  }
+  __syncthreads();  // every wavefront is done with K buffer 0 before tile 2 overwrites it
+
+  // ---- steady state, step t >= 1 (BUF = t & 1): scores of tile t, then PV of tile t-1 on the
+  //      MFMA pipe interleaved with the softmax of tile t on the VALU.
+  auto step = [&](int t, auto buf_c) {
+    constexpr int BUF = decltype(buf_c)::value;
+    if (t + 1 < ntiles) issue_k(t + 1, std::integral_constant<int, BUF ^ 1>{});
+    issue_v(t, std::integral_constant<int, BUF>{});
+    scores(smem + KBUF0 + BUF * TL::KBYTES);
+    mask_scores(S, t);
+    bf16x8 Pn[4];
+    float lacc[2] = {0.f, 0.f};
+    pv(smem + VBUF0 + (BUF ^ 1) * TL::VBYTES, std::true_type{}, Pn, lacc);
+    finish_softmax(Pn, lacc);
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // the loads issued in this step have landed
     __syncthreads();
-    if (tile + 1 >= ntiles) break;
-    if (tile + 2 < ntiles) issue_loads(tile + 2, Stage0{});
-    compute_tile(tile + 1, Stage1{});
-    __builtin_amdgcn_s_waitcnt(0x0F70);
-    __syncthreads();
+  };
+  {
+    int t = 1;
+    for (; t + 1 < ntiles; t += 2) {
+      step(t, B1{});
+      step(t + 1, B0{});
+    }
+    if (t < ntiles) step(t, B1{});
+  }
+  // ---- drain: PV of the last tile
+  {
+    bf16x8 Pn[4];
+    float lacc[2];
+    pv(smem + VBUF0 + ((ntiles - 1) & 1) * TL::VBYTES, std::false_type{}, Pn, lacc);
   }
 
   // ---- epilogue: normalise and write the partial.  Register i of block db is channel
