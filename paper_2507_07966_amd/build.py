@@ -17,10 +17,10 @@ SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
+def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
-    bdir = os.path.join(HERE, "_build")
+    bdir = os.path.join(HERE, "_build", os.path.basename(out))
     os.makedirs(bdir, exist_ok=True)
     procs = []
     for src in SOURCES:
@@ -34,18 +34,18 @@ def build(verbose: bool = False, extra_flags=()) -> str:
         objs.append(obj)
     failed = False
     for src, p in procs:
-        out, _ = p.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l)
+        log, _ = p.communicate()
+        log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
         if p.returncode != 0:
             failed = True
-            print(f"[build] {src} FAILED\n{out}", file=sys.stderr)
-        elif out.strip() and verbose:
-            print(out)
+            print(f"[build] {src} FAILED\n{log}", file=sys.stderr)
+        elif log.strip() and verbose:
+            print(log)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", out]
     subprocess.run(cmd, check=True)
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

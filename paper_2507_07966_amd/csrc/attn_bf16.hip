@@ -47,8 +47,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 #define GLB_PTR(T) __attribute__((address_space(1))) T*
 
 constexpr int BN = KEYS_PER_TILE;  // keys per LDS tile
-constexpr int NTHREADS = 256;
-constexpr int ROWS_PER_WAVE = ROWS_PER_ITEM / 4;
+constexpr int NWAVES = ROWS_PER_ITEM / 32;  // one 32-query MFMA block per wavefront
+constexpr int NTHREADS = NWAVES * 64;
+constexpr int ROWS_PER_WAVE = ROWS_PER_ITEM / NWAVES;
 static_assert(ROWS_PER_WAVE == 32, "one 32-column MFMA block of queries per wavefront");
 // A tile's probabilities are accepted without a maximum search while each lane's partial row
 // sum of the tile stays below SAFE_SUM; every probability is then below 2^16, far inside the
@@ -66,8 +67,9 @@ struct Tile {
   static constexpr int KBYTES = BN * ROWB;
   static constexpr int VBYTES = D * 128;
   static constexpr int STAGE = KBYTES + VBYTES;
-  static constexpr int KBLOCKS_PER_WAVE = KBYTES / 1024 / 4;  // 1 KiB per wavefront-wide load
-  static constexpr int VBLOCKS_PER_WAVE = VBYTES / 1024 / 4;
+  static constexpr int KBLOCKS_PER_WAVE = KBYTES / 1024 / NWAVES;  // 1 KiB per wavefront-wide load
+  static constexpr int VBLOCKS_PER_WAVE = VBYTES / 1024 / NWAVES;
+  static_assert(KBLOCKS_PER_WAVE >= 1 && VBLOCKS_PER_WAVE >= 1, "every wavefront copies at least one block");
 };
 
 __device__ inline int swizzle_term(int row, int rowb) { return rowb == 256 ? (row & 15) : ((row >> 1) & 7); }
@@ -93,7 +95,7 @@ __device__ inline float pair_sum(float x) {
 }
 
 template <int D, bool CAUSAL>
-__global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
+__global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
     float* __restrict__ o_part, float* __restrict__ lse_part, const WorkItem* __restrict__ items,
     const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head, int Hq, int Hkv,
@@ -151,46 +153,46 @@ __global__ __launch_bounds__(NTHREADS, 2) void pass_bf16_kernel(
   for (int ch = 0; ch < 4; ++ch) voff[ch] = l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
 
   // ---- per-lane source of the direct-to-LDS K loads: lane writes LDS chunk `lane` of its block.
-  //      The pointer of tile 0 is kept per load; a tile advances it by a uniform stride.
+  //      Address = uniform tile base (scalar registers) + a per-lane 32-bit byte offset.
   constexpr int LANES_PER_ROW = TL::ROWB / 16, ROWS_PER_BLOCK = 1024 / TL::ROWB;
-  int krow[TL::KBLOCKS_PER_WAVE], kcol[TL::KBLOCKS_PER_WAVE];
-  const __bf16* ksrc[TL::KBLOCKS_PER_WAVE];
+  unsigned koffs[TL::KBLOCKS_PER_WAVE];  // byte offset of this lane's 16 bytes inside a K tile in global memory
 #pragma unroll
   for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
     const int row = (wave * TL::KBLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
-    krow[n] = row;
-    kcol[n] = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;  // logical chunk -> element offset
-    ksrc[n] = kbase + row * row_stride + kcol[n];
+    const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;  // logical chunk -> element offset
+    koffs[n] = (unsigned)((row * row_stride + col) * 2);
   }
-  const __bf16* vsrc0 = vtbase + (wave * TL::VBLOCKS_PER_WAVE) * 512 + lane * 8;
-  const int64_t ktile_stride = (int64_t)BN * row_stride;  // elements per tile of K
+  const int64_t ktile_bytes = (int64_t)BN * row_stride * 2;  // bytes per tile of K in global memory
   const int ntiles = (nkeys + BN - 1) / BN;
   const int full_tiles = nkeys / BN;  // tiles whose 64 keys all exist
 
   auto issue_k = [&](int tile, auto buf_c) {  // K tile -> K buffer buf
     unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
     if (tile < full_tiles) {
-      const int64_t adv = tile * ktile_stride;  // uniform
+      const char* base = reinterpret_cast<const char*>(kbase) + tile * ktile_bytes;  // uniform: lives in SGPRs
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n)
-        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(ksrc[n] + adv),
+        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(base + koffs[n]),
                                          (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
     } else {  // last, partial tile: rows past the end repeat the last key; their scores are masked
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
-        int key = tile * BN + krow[n];
+        const int row = (wave * TL::KBLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
+        const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;
+        int key = tile * BN + row;
         key = key < nkeys ? key : nkeys - 1;
-        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(kbase + key * row_stride + kcol[n]),
+        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(kbase + key * row_stride + col),
                                          (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
       }
     }
   };
+  const unsigned voffs = (unsigned)(((wave * TL::VBLOCKS_PER_WAVE) * 512 + lane * 8) * 2);
   auto issue_v = [&](int tile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
     unsigned char* dst = smem + VBUF0 + decltype(buf_c)::value * TL::VBYTES;
-    const __bf16* vsrc = vsrc0 + (int64_t)tile * (D * BN);
+    const char* base = reinterpret_cast<const char*>(vtbase) + (int64_t)tile * (D * BN * 2);  // uniform
 #pragma unroll
     for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n)
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(vsrc + n * 512),
+      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(base + voffs + n * 1024),
                                        (LDS_PTR(void))(dst + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
   };
 
