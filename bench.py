@@ -28,6 +28,19 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 (published: 2.5 PFLOP/s)
 HBM_PEAK_GBS = 8000.0
 
 
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch of `kernel`, as measured with rocprofv3 hardware counters and recorded
+    in the committed summary profiles/<kernel>_<workload>_hbm_traffic.txt (None if not recorded)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":", 1)[1].split()[0]))
+    except OSError:
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -36,6 +49,9 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="after the timed region also launch plain 256 MiB copy kernels (known HBM bytes, for "
+                         "scaling hardware traffic counters under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -93,6 +109,13 @@ def main():
     kms = np.array([pa.prefix_attn_forward_timed(*fwd_args) for _ in range(args.steps)])
     k_prepass_ms, k_prefix_ms, k_suffix_ms, k_merge_ms = (float(v) for v in kms.mean(axis=0))
 
+    if args.calibrate_copy:
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1.0, out=dst)   # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+
     flop = wl.effective_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
     prefix_flop = 4 * w.head_dim * w.num_q_heads * T * P
@@ -131,12 +154,13 @@ def main():
         "kernel_ms": {"v_layout_prepass": round(k_prepass_ms, 4), "prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
         "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1),
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4), "traffic": None},
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic(w.name, dom_name)},
     }
 
     if not args.no_cpu_baseline:
         from oracle import cref
-        rows_all = wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 4, seed=1)
+        rows_all = wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 96, seed=1)
         rng = np.random.default_rng(2)
         rng.shuffle(rows_all)
 
@@ -152,9 +176,10 @@ def main():
             g = np.searchsorted(off, rows, side="right") - 1
             return int(np.sum(P + (rows - off[g]) + 1))
 
-        probe = rows_all[:2]
+        run_oracle(rows_all[:1])                       # warm the thread pool and the page cache
+        probe = rows_all[:16]
         _, _, thr, t_probe = run_oracle(probe)
-        n = int(max(2, min(len(rows_all), args.cpu_seconds / max(t_probe / 2, 1e-6))))
+        n = int(max(16, min(len(rows_all), args.cpu_seconds / max(t_probe / len(probe), 1e-6))))
         rows = np.sort(rows_all[:n])
         o_ref, l_ref, thr, t_cpu = run_oracle(rows)
         cpu_flop = 4 * w.head_dim * w.num_q_heads * pairs_of(rows)

@@ -1,0 +1,68 @@
+"""Turn rocprofv3 CSV output into the short text summaries kept under profiles/.
+
+  python -m paper_2507_07966_amd.profile_summary stats   <..._kernel_stats.csv>
+  python -m paper_2507_07966_amd.profile_summary counter <..._counter_collection.csv> [--copy-bytes N]
+
+`counter` averages every collected counter per kernel.  For FETCH_SIZE / WRITE_SIZE it also
+scales the reading by what the same counter shows for the plain copy kernels that
+`bench.py --calibrate-copy` launches (each reads and writes --copy-bytes, default 256 MiB),
+which turns counter units into bytes without trusting the documented unit.
+"""
+from __future__ import annotations
+
+import collections
+import csv
+import sys
+
+
+def short_name(k: str) -> str:
+    if "pass_bf16_kernel" in k:
+        return "prefix_pass (bf16 MFMA)" if "Lb0E" in k else "suffix_pass (bf16 MFMA)"
+    if "pass_f32_kernel" in k:
+        return "attention pass (fp32)"
+    if "merge_kernel" in k:
+        return "merge"
+    if "vt_image_kernel" in k:
+        return "v_layout_prepass"
+    if "lse_export" in k:
+        return "lse_export"
+    if "elementwise" in k and "Mul" in k or "mul" in k.lower() and "elementwise" in k:
+        return "plain copy kernel (torch mul by 1)"
+    return k[:60]
+
+
+def stats(path: str) -> None:
+    print(f"{'kernel':40s} {'calls':>6s} {'avg_us':>12s} {'min_us':>12s} {'max_us':>12s} {'pct':>7s}")
+    for r in csv.DictReader(open(path)):
+        print(f"{short_name(r['Name']):40s} {int(r['Calls']):6d} {float(r['AverageNs']) / 1e3:12.2f} "
+              f"{float(r['MinNs']) / 1e3:12.2f} {float(r['MaxNs']) / 1e3:12.2f} {float(r['Percentage']):7.2f}")
+
+
+def counter(path: str, copy_bytes: int) -> None:
+    agg = collections.defaultdict(lambda: collections.defaultdict(list))
+    for r in csv.DictReader(open(path)):
+        agg[short_name(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+    means = {k: {c: sum(v) / len(v) for c, v in d.items()} for k, d in agg.items()}
+    for k, d in means.items():
+        n = len(next(iter(agg[k].values())))
+        print(f"{k:40s} dispatches={n:3d} " + " ".join(f"{c}={v:.6g}" for c, v in sorted(d.items())))
+    copy = next((d for k, d in means.items() if k.startswith("plain copy kernel")), None)
+    if copy:
+        for c in ("FETCH_SIZE", "WRITE_SIZE"):
+            if c in copy and copy[c] > 0:
+                scale = copy_bytes / copy[c]
+                print(f"\n{c}: the copy kernel moves {copy_bytes} bytes and reads {copy[c]:.6g} counter units "
+                      f"=> {scale:.4f} bytes per unit")
+                for k, d in means.items():
+                    if c in d:
+                        print(f"  {k:40s} {c} = {d[c] * scale / 1e6:12.2f} MB per dispatch")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) < 3 or sys.argv[1] not in ("stats", "counter"):
+        sys.exit(__doc__)
+    if sys.argv[1] == "stats":
+        stats(sys.argv[2])
+    else:
+        cb = int(sys.argv[sys.argv.index("--copy-bytes") + 1]) if "--copy-bytes" in sys.argv else 256 * 1024 * 1024
+        counter(sys.argv[2], cb)
