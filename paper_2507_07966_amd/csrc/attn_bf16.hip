@@ -8,11 +8,11 @@
 // the same prefix keys/values; only the prompt+response part differs (Sec. 4.2, Sec. 5.2).
 //
 // Mapping onto the hardware
-//   - A workgroup (4 wavefronts) owns ROWS_PER_ITEM = 128 stacked rows
+//   - A workgroup (8 wavefronts) owns ROWS_PER_ITEM = 256 stacked rows
 //     m = i * group + (h % group) of one (kv head, rollout): the q heads of a GQA group and
-//     consecutive positions are stacked, so every K/V tile staged in LDS serves 128 rows.
-//     Each wavefront owns 32 rows.  Two workgroups share a CU (<= 256 registers, 64 KiB LDS
-//     each), so one wavefront's softmax VALU work overlaps the other's MFMA work.
+//     consecutive positions are stacked, so every K/V tile staged in LDS serves 256 rows.
+//     Each wavefront owns 32 rows; two wavefronts share a SIMD (<= 256 registers each), so one
+//     wavefront's softmax VALU work also overlaps the other's MFMA work.
 //   - K tiles and the pre-transposed V tile images go global -> LDS with direct-to-LDS
 //     16-byte loads (no staging registers), double buffered, one barrier per tile.  The LDS
 //     layouts are XOR-swizzled so every 16-byte operand read is bank-conflict free.

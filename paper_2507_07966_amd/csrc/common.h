@@ -12,7 +12,10 @@ namespace pa {
 
 // Tile geometry of the two attention passes: one work item = ROWS_PER_ITEM stacked query
 // rows of one (kv head, rollout); keys are swept in LDS tiles of KEYS_PER_TILE.
-constexpr int ROWS_PER_ITEM = 128;
+#ifndef PA_ROWS_PER_ITEM
+#define PA_ROWS_PER_ITEM 256
+#endif
+constexpr int ROWS_PER_ITEM = PA_ROWS_PER_ITEM;
 constexpr int KEYS_PER_TILE = 64;
 constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
 
