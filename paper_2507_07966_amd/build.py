@@ -13,9 +13,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprefix_attn.so")
 SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip", "merge.hip"]
-# packed-fp32 code generation is switched off for every device translation unit; MFMA results are
-# kept in architectural VGPRs (the softmax reads them with VALU instructions, which cannot read AGPRs)
-DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
+# packed-fp32 code generation is switched off for every device translation unit
+DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
