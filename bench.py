@@ -126,7 +126,7 @@ def main():
         dom_name, dom_flop, dom_ms = "suffix_pass", suffix_flop, k_suffix_ms
     achieved = dom_flop / (dom_ms * 1e-3) * 1e-12
     e = 2 if w.dtype == "bf16" else 4
-    merge_bytes = T * w.num_q_heads * (w.head_dim * (8 + e) + 12)
+    merge_bytes = T * w.num_q_heads * (w.head_dim * ((8 if P else 4) + e) + (12 if P else 8))
     result = {
         "metric": "effective attention TFLOP/s",
         "value": round(tflops, 2),

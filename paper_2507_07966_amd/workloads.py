@@ -55,6 +55,10 @@ WORKLOADS = {
     "C4": Workload("C4", "bf16", 28, 4, 128, 3600, 64, 256, 8, 2048, note="hour-long video, 230K prefix"),
     "C5": Workload("C5", "bf16", 28, 4, 128, 8192, 64, 512, 16, None, response_range=(256, 4096),
                    note="max frames, 512K prefix, ragged rollouts"),
+    # The other half of "computed once": causal self-attention of the 512-frame video prefix itself
+    # (P = 0, one sequence of 32,768 video tokens), run once per layer and shared by all rollouts.
+    "N1": Workload("N1", "bf16", 28, 4, 128, 0, 64, 0, 1, 32768,
+                   note="shared prefix self-attention: 32K video tokens, causal, no rollouts"),
 }
 
 

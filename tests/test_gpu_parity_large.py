@@ -51,3 +51,9 @@ def test_c4_hour_long_sampled_rows():
 def test_c5_max_frames_ragged_sampled_rows():
     x, out, lse = sampled_parity("C5", n_random=2, stride=1024)
     assert len(set(x.suffix_lens.tolist())) > 8   # really ragged
+
+
+def test_n1_prefix_self_attention_sampled_rows():
+    """Causal self-attention of the 32K-token video prefix (P = 0, one sequence): the same library
+    call, exercised as one long packed sequence whose rows cross hundreds of work items."""
+    sampled_parity("N1", n_random=64, stride=4096)
