@@ -88,3 +88,47 @@ def test_c2_full_tensor():
     out, lse = run_hip(x)
     ro, rl = oracle_full(x)
     check(out, lse, ro, rl, "C2")
+
+
+def test_non_default_stream_and_graph_replay():
+    """forward + lse only enqueue work and allocate nothing, so they can run on any stream and be
+    captured into a HIP graph; every replay must reproduce the eager result bit for bit."""
+    import torch
+    import paper_2507_07966_amd as pa
+    from tests.gpu_util import to_device
+
+    x = wl.make_custom("bf16", 28, 4, 128, 700, (300, 129), seed=9)
+    w = x.workload
+    eager_out, eager_lse = run_hip(x)
+    dev = {n: to_device(x, n) for n in ("q", "k_prefix", "v_prefix", "k_suffix", "v_suffix")}
+    plan = pa.prefix_attn_plan(w.num_q_heads, w.num_kv_heads, w.head_dim, w.prefix_len, x.suffix_lens, w.scale,
+                               dtype="bf16", device=0)
+    T = x.total_suffix
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    out = torch.zeros((T, 28, 128), dtype=torch.bfloat16, device="cuda")
+    lse = torch.zeros((28, T), dtype=torch.float32, device="cuda")
+
+    def enqueue():
+        pa.prefix_attn_forward(plan, dev["q"], dev["k_prefix"], dev["v_prefix"], dev["k_suffix"], dev["v_suffix"], out, ws)
+        pa.prefix_attn_lse(plan, ws, lse)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()
+    side.synchronize()
+    assert np.array_equal(out.float().cpu().numpy(), eager_out) and np.array_equal(lse.cpu().numpy(), eager_lse)
+
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(3):
+        out.zero_()
+        lse.zero_()
+        ws.random_(0, 255)          # stale workspace contents must not matter
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(out.float().cpu().numpy(), eager_out), f"replay {rep}"
+        assert np.array_equal(lse.cpu().numpy().astype(np.float64), eager_lse), f"replay {rep}"
+    plan.destroy()
