@@ -254,7 +254,10 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
 
   f32x16 S[2];    // scores of the tile being soft-maxed
   bf16x8 Pb[4];   // probabilities of the previous tile, [16-key chunk]: B operand of the PV product
-  auto scores = [&](const unsigned char* kbuf) {  // S^T = K Q^T, operand reads PF steps ahead of the MFMAs
+  // S^T = K Q^T, operand reads PF steps ahead of the MFMAs.  mid(kk) runs after contraction step
+  // kk: the steady state uses it to issue the next tile's loads inside the MFMA stream instead
+  // of as one burst.
+  auto scores = [&](const unsigned char* kbuf, auto&& mid) {
     zero(S);
     constexpr int PF = 2;
     bf16x8 ka[KK][2];
@@ -271,6 +274,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
       }
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb) S[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka[kk][kb], Q[kk], S[kb], 0, 0, 0);
+      mid(kk);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   if (ntiles > 1) issue_k(1, B1{});
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
-  scores(smem + KBUF0);
+  scores(smem + KBUF0, [](int) {});
   mask_scores(S, 0);
   mref = row_max(S);  // finite: key 0 is visible to every row
   {
@@ -350,9 +354,10 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   //      MFMA pipe interleaved with the softmax of tile t on the VALU.
   auto step = [&](int t, auto buf_c) {
     constexpr int BUF = decltype(buf_c)::value;
-    if (t + 1 < ntiles) issue_k(t + 1, std::integral_constant<int, BUF ^ 1>{});
-    issue_v(t, std::integral_constant<int, BUF>{});
-    scores(smem + KBUF0 + BUF * TL::KBYTES);
+    scores(smem + KBUF0 + BUF * TL::KBYTES, [&](int kk) {
+      if (kk == KK / 8 && t + 1 < ntiles) issue_k(t + 1, std::integral_constant<int, BUF ^ 1>{});
+      if (kk == KK / 2 + KK / 8) issue_v(t, std::integral_constant<int, BUF>{});
+    });
     mask_scores(S, t);
     bf16x8 Pn[4];
     float lacc[2] = {0.f, 0.f};
