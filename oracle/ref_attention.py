@@ -27,7 +27,8 @@ rescaling and no merge of partial results in `prefix_shared_attention`.
 Pins (tests/test_oracle_pins.py): row sums, uniform-score closed form, causality,
 equality with brute-force full-sequence attention, torch SDPA on the concatenated
 sequence, rollout isolation, prefix permutation, key shift, split/merge identity,
-single key, peaked row, GQA-vs-repeated-KV.
+single key, peaked row, GQA-vs-repeated-KV.  The backward (bottom of this file) is
+pinned by finite differences of the forward, torch autograd, closed forms and invariants.
 """
 from __future__ import annotations
 
@@ -190,3 +191,57 @@ def merge_partials(o1, lse1, o2, lse2):
         a1 = np.where(tot > 0, w1 / tot, 0.0)
         a2 = np.where(tot > 0, w2 / tot, 0.0)
     return a1[:, None] * o1 + a2[:, None] * o2, lse
+
+
+# ----------------------------------------------------------------------------------------------
+# Backward.  The policy model is trained through the attention (paper Eq. 1 is maximised by
+# gradient ascent on the policy's token probabilities; Sec. 5.2 prefills every rollout with the
+# policy model), so the gradient of a scalar objective L with respect to the attention inputs is
+# needed, given dO = dL/dO.  What follows is the chain rule applied to the forward definition
+# at the top of this file, one (rollout, head) at a time, in fp64:
+#
+#     W   = softmax(s) over the visible keys            (row-wise; `attention_weights`)
+#     dV  = W^T dO
+#     dW  = dO V^T
+#     dS  = W * (dW - rowsum(W * dW))                   (Jacobian of a row-wise softmax)
+#     dQ  = scale * dS K,      dK = scale * dS^T Q
+#
+# A kv head receives the sum over the q heads of its group; a *prefix* key/value additionally
+# receives the sum over all G rollouts, because every rollout attends to the same cached prefix
+# (Sec. 5.1).  The LSE output is treated as a saved statistic, not as a differentiated output.
+# Pinned against central finite differences of `prefix_shared_attention`, torch autograd on the
+# concatenated sequences, closed forms and invariants (tests/test_oracle_pins.py).
+
+def prefix_shared_attention_backward(q, k_prefix, v_prefix, k_suffix, v_suffix, suffix_lens, scale, d_out):
+    """Gradients of L = sum(d_out * out) with respect to the five inputs.
+
+    d_out [T,Hq,D].  Returns (dq [T,Hq,D], dk_prefix [P,Hkv,D], dv_prefix [P,Hkv,D],
+    dk_suffix [T,Hkv,D], dv_suffix [T,Hkv,D]), all float64.
+    """
+    q, k_prefix, v_prefix = _as64(q), _as64(k_prefix), _as64(v_prefix)
+    k_suffix, v_suffix, d_out = _as64(k_suffix), _as64(v_suffix), _as64(d_out)
+    T, Hq, D = q.shape
+    P, Hkv, _ = k_prefix.shape
+    r = Hq // Hkv
+    off = suffix_offsets(suffix_lens)
+    dq = np.zeros_like(q)
+    dkp, dvp = np.zeros_like(k_prefix), np.zeros_like(v_prefix)
+    dks, dvs = np.zeros_like(k_suffix), np.zeros_like(v_suffix)
+    for g in range(len(suffix_lens)):
+        a, b = int(off[g]), int(off[g + 1])
+        for h in range(Hq):
+            c = h // r
+            w, _ = attention_weights(q, k_prefix, k_suffix, suffix_lens, scale, g, h)   # [S, P+S]
+            keys = np.concatenate([k_prefix[:, c, :], k_suffix[a:b, c, :]], axis=0)
+            vals = np.concatenate([v_prefix[:, c, :], v_suffix[a:b, c, :]], axis=0)
+            do = d_out[a:b, h, :]
+            dvals = w.T @ do
+            dw = do @ vals.T
+            ds = w * (dw - (w * dw).sum(axis=1, keepdims=True))
+            dq[a:b, h, :] = scale * (ds @ keys)
+            dkeys = scale * (ds.T @ q[a:b, h, :])
+            dkp[:, c, :] += dkeys[:P]
+            dvp[:, c, :] += dvals[:P]
+            dks[a:b, c, :] += dkeys[P:]
+            dvs[a:b, c, :] += dvals[P:]
+    return dq, dkp, dvp, dks, dvs
