@@ -112,6 +112,51 @@ int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, con
 int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out,
                     void* hip_stream);
 
+/* ---- backward (the policy model is trained through this attention: paper Eq. 1, Sec. 5.2) ----
+ *
+ * Given d_out = dL/d(out), computes the gradients of L with respect to the five inputs of the
+ * forward call.  With W the softmax weights of a query row over its visible keys,
+ *   dV_j = sum_rows W_j dO,   dS_j = W_j (<dO, v_j> - <dO, O>),
+ *   dQ   = scale sum_j dS_j k_j,   dK_j = scale sum_rows dS_j q,
+ * where a kv head sums over the q heads of its group and a PREFIX key/value additionally sums
+ * over all G rollouts, because every rollout attends to the same cached video prefix
+ * (Sec. 5.1).  The LSE is treated as a saved statistic, not as a differentiated output. */
+
+/* Bytes of backward workspace a plan needs (per-row statistics; for bf16 also re-laid-out
+ * copies of Q, dO and K). */
+int prefix_attn_backward_workspace(const prefix_attn_plan_t* plan, size_t* workspace_bytes_out);
+
+/* Enqueue the backward on `hip_stream`.  All tensors are DEVICE pointers, 16-byte aligned, in
+ * the plan's dtype, with the shapes of the forward call:
+ *   q, k_prefix, v_prefix, k_suffix, v_suffix   the forward inputs, unchanged
+ *   out    [T, Hq, D]   the forward output
+ *   d_out  [T, Hq, D]   gradient of the objective with respect to `out`
+ *   lse    [Hq, T]      fp32 log-sum-exp of the forward call on these inputs, as written by
+ *                       prefix_attn_lse (the saved softmax statistic)
+ *   dq [T, Hq, D], dk_prefix, dv_prefix [P, Hkv, D] (may be NULL when P == 0),
+ *   dk_suffix, dv_suffix [T, Hkv, D]             outputs, fully overwritten
+ *   workspace           scratch of at least prefix_attn_backward_workspace bytes (the forward
+ *                       workspace is not needed and may be reused for it if large enough)
+ * Every gradient element is produced by exactly one workgroup in a fixed order (no atomics),
+ * so results are bitwise reproducible.  Argument errors are reported before anything is
+ * launched. */
+int prefix_attn_backward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                         const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                         const void* out, const void* d_out, const float* lse, void* dq,
+                         void* dk_prefix, void* dv_prefix, void* dk_suffix, void* dv_suffix,
+                         void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Measurement variant: same arguments and result, but the stages are bracketed by HIP events
+ * and the call WAITS for them.  kernel_ms (HOST [4]) receives the durations in milliseconds of
+ * {pre-pass (delta, layouts), dQ pass, dK/dV pass over the prefix keys, dK/dV pass over the
+ * rollouts' own keys}; for fp32 plans entry 2 is the whole dK/dV kernel and entry 3 is ~0. */
+int prefix_attn_backward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                               const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                               const void* out, const void* d_out, const float* lse,
+                               void* dq, void* dk_prefix, void* dv_prefix, void* dk_suffix,
+                               void* dv_suffix, void* workspace, size_t workspace_bytes,
+                               void* hip_stream, float* kernel_ms);
+
 /* Release a plan (NULL is allowed).  Work enqueued with the plan must have finished. */
 void prefix_attn_destroy(prefix_attn_plan_t* plan);
 
@@ -131,6 +176,12 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
  * {rollout g (-1 = padding item), first stacked row inside the rollout, kv head c,
  *  number of keys the item sweeps}. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
+
+/* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding
+ * entries included: {rollout g (-1 for prefix keys), first key of the block, kv head c (-1 =
+ * padding entry), number of keys in the block}. */
+int64_t prefix_attn_plan_num_key_items(const prefix_attn_plan_t* plan, int32_t pass);
+int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
 /* Total suffix tokens T of the plan. */
 int64_t prefix_attn_plan_total_tokens(const prefix_attn_plan_t* plan);

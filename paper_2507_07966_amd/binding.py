@@ -23,7 +23,9 @@ STATUS_NAMES = {0: "PA_OK", 1: "PA_ERR_NULL", 2: "PA_ERR_SHAPE", 3: "PA_ERR_UNSU
                 5: "PA_ERR_WORKSPACE", 6: "PA_ERR_ALLOC", 7: "PA_ERR_HIP"}
 EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed", "prefix_attn_lse", "prefix_attn_destroy",
                     "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
-                    "prefix_attn_plan_items", "prefix_attn_plan_total_tokens")
+                    "prefix_attn_plan_items", "prefix_attn_plan_total_tokens", "prefix_attn_backward_workspace",
+                    "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_plan_num_key_items",
+                    "prefix_attn_plan_key_items")
 
 
 class PrefixAttnError(RuntimeError):
@@ -73,6 +75,16 @@ def load_library():
     lib.prefix_attn_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.prefix_attn_plan_total_tokens.restype = ctypes.c_int64
     lib.prefix_attn_plan_total_tokens.argtypes = [vp]
+    lib.prefix_attn_backward_workspace.restype = ctypes.c_int
+    lib.prefix_attn_backward_workspace.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.prefix_attn_backward.restype = ctypes.c_int
+    lib.prefix_attn_backward.argtypes = [vp] * 15 + [sz, vp]
+    lib.prefix_attn_backward_timed.restype = ctypes.c_int
+    lib.prefix_attn_backward_timed.argtypes = [vp] * 15 + [sz, vp, ctypes.POINTER(ctypes.c_float)]
+    lib.prefix_attn_plan_num_key_items.restype = ctypes.c_int64
+    lib.prefix_attn_plan_num_key_items.argtypes = [vp, ctypes.c_int32]
+    lib.prefix_attn_plan_key_items.restype = ctypes.c_int
+    lib.prefix_attn_plan_key_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -117,6 +129,27 @@ class PrefixAttnPlan:
             st = lib.prefix_attn_plan_items(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
             if st:
                 raise PrefixAttnError(st, "prefix_attn_plan_items")
+        return out
+
+    @property
+    def backward_workspace_bytes(self) -> int:
+        n = ctypes.c_size_t()
+        st = load_library().prefix_attn_backward_workspace(self.handle, ctypes.byref(n))
+        if st:
+            raise PrefixAttnError(st, "prefix_attn_backward_workspace")
+        return int(n.value)
+
+    def key_items(self, which: int) -> np.ndarray:
+        """dK/dV work list, 0 (prefix key blocks) or 1 (suffix key blocks): int32 [n, 4] = (g, key0, c, nkeys)."""
+        lib = load_library()
+        n = lib.prefix_attn_plan_num_key_items(self.handle, which)
+        if n < 0:
+            raise PrefixAttnError(2, "prefix_attn_plan_num_key_items")
+        out = np.zeros((n, 4), dtype=np.int32)
+        if n:
+            st = lib.prefix_attn_plan_key_items(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+            if st:
+                raise PrefixAttnError(st, "prefix_attn_plan_key_items")
         return out
 
     def destroy(self):
@@ -199,6 +232,42 @@ def prefix_attn_lse(plan: PrefixAttnPlan, workspace, lse_out, stream=None) -> No
     st = load_library().prefix_attn_lse(plan.handle, _ptr(workspace), _ptr(lse_out), _stream(stream))
     if st:
         raise PrefixAttnError(st, "prefix_attn_lse")
+
+
+def _nbytes(t, default):
+    return t.numel() * t.element_size() if hasattr(t, "numel") else default
+
+
+def _backward_args(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, d_out, lse, dq, dk_prefix,
+                   dv_prefix, dk_suffix, dv_suffix, workspace, stream):
+    return (plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix), _ptr(v_suffix), _ptr(out),
+            _ptr(d_out), _ptr(lse), _ptr(dq), _ptr(dk_prefix), _ptr(dv_prefix), _ptr(dk_suffix),
+            _ptr(dv_suffix), _ptr(workspace), _nbytes(workspace, plan.backward_workspace_bytes), _stream(stream))
+
+
+def prefix_attn_backward(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, d_out,
+                         lse, dq, dk_prefix, dv_prefix, dk_suffix, dv_suffix, workspace,
+                         stream=None) -> None:
+    """prefix_attn_backward of the C ABI.  `lse` is the [Hq, T] fp32 tensor written by prefix_attn_lse after the forward call on the
+    same inputs; `workspace` is a uint8 tensor of at least plan.backward_workspace_bytes.  Enqueues only."""
+    st = load_library().prefix_attn_backward(*_backward_args(
+        plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, d_out, lse, dq, dk_prefix, dv_prefix,
+        dk_suffix, dv_suffix, workspace, stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_backward")
+
+
+def prefix_attn_backward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, d_out,
+                               lse, dq, dk_prefix, dv_prefix, dk_suffix, dv_suffix, workspace,
+                               stream=None):
+    """prefix_attn_backward_timed of the C ABI.  Waits; returns (prepass_ms, dq_ms, dkv_prefix_ms, dkv_suffix_ms)."""
+    ms = (ctypes.c_float * 4)()
+    st = load_library().prefix_attn_backward_timed(*_backward_args(
+        plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, d_out, lse, dq, dk_prefix, dv_prefix,
+        dk_suffix, dv_suffix, workspace, stream), ms)
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_backward_timed")
+    return float(ms[0]), float(ms[1]), float(ms[2]), float(ms[3])
 
 
 def prefix_attn_destroy(plan: PrefixAttnPlan) -> None:

@@ -12,7 +12,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprefix_attn.so")
-SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip", "merge.hip"]
+SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip", "merge.hip",
+           "bwd_api.cpp", "bwd_prep.hip", "bwd_dq_bf16.hip", "bwd_dkv_bf16.hip", "bwd_f32.hip"]
 # packed-fp32 code generation is switched off for every device translation unit
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -1,0 +1,218 @@
+// Backward, key-stationary pass (bf16 MFMA, gfx950): dK and dV.
+//
+// A workgroup owns 128 keys of one kv head (4 wavefronts x 32 keys; K and V columns stay in
+// registers) and streams the stacked query rows that see those keys past them, 64 rows per
+// tile.  For the shared video prefix these are the rows of ALL rollouts (paper Sec. 5.1: one
+// cached prefix for every rollout), so the sum over rollouts happens in the accumulators and
+// each prefix key is written exactly once, with no atomics.  For a rollout's own keys the rows
+// are the rollout's later positions (causal).  Per 32-row block:
+//   S  = Q K^T                   (A = Q rows from LDS,  B = K in registers)
+//   dW = dO V^T                  (A = dO rows from LDS, B = V in registers)
+//   W  = exp2(c S - LSE log2 e),  dS = W * (dW - delta)   (VALU; LSE/delta per row from LDS)
+//   dV^T += dO^T W               (A = transposed dO image, B = W packed to bf16)
+//   dK^T += Q^T dS               (A = transposed Q image,  B = dS packed to bf16)
+// The stacked, row-major Q/dO copies and their transposed images come from the pre-pass; a
+// tile (4 x 16 KiB + statistics) goes global -> LDS with direct-to-LDS loads, double buffered,
+// one barrier per tile.  One wavefront per SIMD: the accumulators (128 registers) and the K/V
+// columns (64) need more than half of the register file.
+#include <hip/hip_runtime.h>
+
+#include "bwd.h"
+#include "mfma_tiles.h"
+
+namespace pa {
+namespace {
+
+using namespace mt;
+
+constexpr int KV_THREADS = KEY_WAVES * 64;
+constexpr float LOG2E = 1.4426950408889634f;
+
+template <int D, bool CAUSAL>
+__global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
+    const __bf16* __restrict__ k, const __bf16* __restrict__ v, const __bf16* __restrict__ qs,
+    const __bf16* __restrict__ dos, const __bf16* __restrict__ qst, const __bf16* __restrict__ dost,
+    const float* __restrict__ lse2s, const float* __restrict__ deltas, const int32_t* __restrict__ toks,
+    __bf16* __restrict__ dk,
+    __bf16* __restrict__ dv, const KeyItem* __restrict__ items, const int32_t* __restrict__ cu, int64_t T,
+    int64_t Mpad, int Hkv, int group, float scale) {
+  using G = Geo<D>;
+  constexpr int KK = G::KK, DB = G::DB;
+  constexpr int STATS = 1024;  // per row: LSE*log2e, delta, packed token index (3 x 64 words)
+  constexpr int STAGE = 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES + STATS;
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * STAGE];
+
+  const KeyItem it = items[blockIdx.x];
+  if (it.c < 0) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int off_g = CAUSAL ? cu[it.g] : 0;
+  const int end_g = CAUSAL ? cu[it.g + 1] : 0;
+  const int64_t row_stride = (int64_t)Hkv * D;
+
+  // ---- this lane's key column: K and V in registers (zeros past the end of the block)
+  const int kloc = wave * 32 + l32;        // key inside the block
+  const int key = it.key0 + kloc;          // prefix index, or position inside the rollout
+  const bool key_ok = kloc < it.nkeys;
+  const int64_t krow = (int64_t)(off_g + key) * Hkv + it.c;  // row of k / v / dk / dv
+  bf16x8 Kb[KK], Vb[KK];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) {
+    if (key_ok) {
+      Kb[kk] = *reinterpret_cast<const bf16x8*>(k + krow * D + 16 * kk + 8 * hf);
+      Vb[kk] = *reinterpret_cast<const bf16x8*>(v + krow * D + 16 * kk + 8 * hf);
+    } else {
+      Kb[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      Vb[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+  }
+  const float c_log2 = scale * LOG2E;
+
+  int roff[KK], ioff[4];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) roff[kk] = row_operand_offset<D>(l32, hf, kk);
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) ioff[ch] = image_operand_offset(l32, hf, ch);
+
+  // ---- row tiles: stacked rows M = t * group + j of kv head c, 64 per tile, numbered over all packed tokens
+  const int64_t m_begin = CAUSAL ? (int64_t)(off_g + it.key0) * group : 0;
+  const int64_t m_end = CAUSAL ? (int64_t)end_g * group : T * group;
+  const int tile0 = (int)(m_begin / TILE);
+  const int tile1 = (int)((m_end + TILE - 1) / TILE);
+  const int64_t head_rows = (int64_t)it.c * Mpad;
+  const __bf16* qs_c = qs + head_rows * D;
+  const __bf16* dos_c = dos + head_rows * D;
+  const __bf16* qst_c = qst + head_rows * D;   // image n starts at n * 64 * D elements
+  const __bf16* dost_c = dost + head_rows * D;
+  const float* lse_c = lse2s + head_rows;
+  const float* del_c = deltas + head_rows;
+
+  const int* tok_c = toks + head_rows;
+  // rows visible to this lane's key in the causal pass: packed tokens tkey .. end_g - 1
+  const unsigned tkey = (unsigned)(off_g + key);
+  const unsigned tspan = (unsigned)(end_g - (off_g + key));
+
+  auto issue = [&](int tile, int buf) {
+    unsigned char* dst = smem + buf * STAGE;
+    const int64_t e0 = (int64_t)tile * TILE * D;  // first element of the tile in each of the four arrays
+    if (wave == 0) {  // per-row statistics: 64 dwords each, lane l's word lands at word l
+      unsigned char* st = dst + 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES;
+      const int64_t m = (int64_t)tile * TILE + lane;
+      __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(lse_c + m), (PA_LDS_PTR(void))st, 4, 0, 0);
+      __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(del_c + m), (PA_LDS_PTR(void))(st + TILE * 4), 4, 0, 0);
+      if (CAUSAL)
+        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(tok_c + m), (PA_LDS_PTR(void))(st + 2 * TILE * 4), 4, 0, 0);
+    }
+    issue_row_tile<D, KEY_WAVES>(dst, qs_c + e0, D, TILE, wave, lane);
+    issue_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, D, TILE, wave, lane);
+    issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, qst_c + e0, wave, lane);
+    issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, dost_c + e0, wave, lane);
+  };
+
+  f32x16 dK[DB], dV[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      dK[db][i] = 0.f;
+      dV[db][i] = 0.f;
+    }
+
+  if (tile0 < tile1) issue(tile0, 0);
+  for (int tile = tile0; tile < tile1; ++tile) {
+    const int buf = (tile - tile0) & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS loads of this wavefront have landed
+    __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
+    if (tile + 1 < tile1) issue(tile + 1, buf ^ 1);
+    const unsigned char* qt = smem + buf * STAGE;
+    const unsigned char* dt = qt + G::ROW_TILE_BYTES;
+    const unsigned char* qim = qt + 2 * G::ROW_TILE_BYTES;
+    const unsigned char* dim = qim + G::IMAGE_BYTES;
+    const float* st = reinterpret_cast<const float*>(dim + G::IMAGE_BYTES);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      f32x16 S, W;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        S[i] = 0.f;
+        W[i] = 0.f;
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 qa = lds_operand(qt + rb * 32 * G::ROWB + roff[kk]);
+        const bf16x8 da = lds_operand(dt + rb * 32 * G::ROWB + roff[kk]);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, Kb[kk], S, 0, 0, 0);
+        W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, Vb[kk], W, 0, 0, 0);
+      }
+      // register i: row rb*32 + 8*(i/4) + 4*hf + i%4 of the tile, this lane's key
+      bf16x8 Pb[2], dSb[2];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const int r0 = rb * 32 + 8 * a + 4 * hf;
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + r0);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + TILE + r0);
+        i32x4 p4 = {0, 0, 0, 0};
+        if (CAUSAL) p4 = *reinterpret_cast<const i32x4*>(st + 2 * TILE + r0);
+        float p[4], ds[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * a + e;
+          p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -l4[e]));
+          if (CAUSAL && (unsigned)p4[e] - tkey >= tspan) p[e] = 0.f;
+          ds[e] = p[e] * (W[i] - d4[e]);
+        }
+        pack4(p, 4 * a, Pb);
+        pack4(ds, 4 * a, dSb);
+      }
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 da = lds_operand(dim + db * 32 * 128 + ioff[2 * rb + c2]);
+          const bf16x8 qa = lds_operand(qim + db * 32 * 128 + ioff[2 * rb + c2]);
+          dV[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, Pb[c2], dV[db], 0, 0, 0);
+          dK[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dSb[c2], dK[db], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's key
+  if (key_ok) {
+    __bf16* kp = dk + krow * D + 4 * hf;
+    __bf16* vp = dv + krow * D + 4 * hf;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const f32x4 wk = {dK[db][4 * a] * scale, dK[db][4 * a + 1] * scale, dK[db][4 * a + 2] * scale,
+                          dK[db][4 * a + 3] * scale};
+        const f32x4 wv = {dV[db][4 * a], dV[db][4 * a + 1], dV[db][4 * a + 2], dV[db][4 * a + 3]};
+        *reinterpret_cast<bf16x4*>(kp + db * 32 + 8 * a) = __builtin_convertvector(wk, bf16x4);
+        *reinterpret_cast<bf16x4*>(vp + db * 32 + 8 * a) = __builtin_convertvector(wv, bf16x4);
+      }
+  }
+}
+
+}  // namespace
+
+int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream) {
+  if (a.num_items == 0) return 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
+  const unsigned grid = (unsigned)a.num_items;
+#define PA_LAUNCH(DD, CC)                                                                                        \
+  bwd_dkv_kernel<DD, CC><<<grid, KV_THREADS, 0, s>>>(b(a.k), b(a.v), b(a.qs), b(a.dos), b(a.qst), b(a.dost),     \
+                                                     a.lse2s, a.deltas, a.toks, static_cast<__bf16*>(a.dk),      \
+                                                     static_cast<__bf16*>(a.dv), a.items, a.cu, a.T, a.Mpad,    \
+                                                     a.Hkv, a.group, a.scale)
+  if (a.D == 128) {
+    if (a.causal) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
+  } else {
+    if (a.causal) PA_LAUNCH(64, true); else PA_LAUNCH(64, false);
+  }
+#undef PA_LAUNCH
+  return (int)hipGetLastError();
+}
+
+}  // namespace pa

@@ -1,0 +1,205 @@
+// Backward, query-stationary pass (bf16 MFMA, gfx950): dQ of every suffix token.
+//
+// A workgroup owns the same 256 stacked rows (8 wavefronts x 32 rows of one rollout and kv
+// head) as in the forward passes and sweeps first the shared prefix keys (paper Sec. 5.1: one
+// cached video prefix for all rollouts) and then the rollout's own keys up to the diagonal.
+// Because the softmax statistics are saved (LSE) no online rescaling is needed, so prefix and
+// suffix keys accumulate into one dQ and nothing has to be merged.  Per 32-key block:
+//   S^T  = K Q^T                 (A = K tile rows from LDS,      B = Q in registers)
+//   dW^T = V dO^T                (A = V tile rows from LDS,      B = dO in registers)
+//   dS^T = W^T * (dW^T - delta),  W = exp2(c S - LSE log2 e)      (VALU, per lane = per query)
+//   dQ^T += K^T dS^T             (A = transposed K image in LDS, B = dS^T packed to bf16)
+// K, V tiles and the K^T image go global -> LDS with direct-to-LDS loads, double buffered, one
+// barrier per 64-key tile.
+#include <hip/hip_runtime.h>
+
+#include "bwd.h"
+#include "mfma_tiles.h"
+
+namespace pa {
+namespace {
+
+using namespace mt;
+
+constexpr int DQ_WAVES = ROWS_PER_ITEM / 32;
+constexpr int DQ_THREADS = DQ_WAVES * 64;
+
+template <int D>
+__global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
+    const __bf16* __restrict__ q, const __bf16* __restrict__ d_out, const __bf16* __restrict__ k_prefix,
+    const __bf16* __restrict__ v_prefix, const __bf16* __restrict__ k_suffix, const __bf16* __restrict__ v_suffix,
+    const __bf16* __restrict__ kt_prefix, const __bf16* __restrict__ kt_suffix, const float* __restrict__ lse2s,
+    const float* __restrict__ deltas, int64_t Mpad, __bf16* __restrict__ dq, const WorkItem* __restrict__ items,
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int P, int tiles_prefix, int tiles_suffix,
+    int Hq, int Hkv, int group, float scale) {
+  using G = Geo<D>;
+  constexpr int KK = G::KK, DB = G::DB;
+  constexpr int STAGE = 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES;  // K tile, V tile, K^T image
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * STAGE];
+
+  const WorkItem it = items[blockIdx.x];
+  if (it.g < 0) return;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int off_g = cu[it.g];
+  const int S_g = cu[it.g + 1] - off_g;
+  const int nrows = S_g * group;
+  const int nkeys = it.nkeys;  // causal extent of the item's last row
+  const int64_t row_stride = (int64_t)Hkv * D;
+
+  // ---- this lane's query: Q and dO columns, LSE and delta
+  bf16x8 Q[KK], dOb[KK];
+  int pos;        // suffix position of the query (causal bound)
+  int64_t orow;   // packed (token, head) row, -1 past the end
+  float lse2 = 0.f, dl = 0.f;
+  {
+    const int m = it.row0 + wave * 32 + l32;
+    if (m < nrows) {
+      const int i = m / group, hh = m - i * group;
+      pos = i;
+      orow = (int64_t)(off_g + i) * Hq + it.c * group + hh;
+      const __bf16* qp = q + orow * D + 8 * hf;
+      const __bf16* dp = d_out + orow * D + 8 * hf;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        Q[kk] = *reinterpret_cast<const bf16x8*>(qp + 16 * kk);
+        dOb[kk] = *reinterpret_cast<const bf16x8*>(dp + 16 * kk);
+      }
+      const int64_t srow = (int64_t)it.c * Mpad + (int64_t)off_g * group + m;  // stacked row over all packed tokens
+      lse2 = lse2s[srow];
+      dl = deltas[srow];
+    } else {
+      pos = -1;  // sees nothing: every weight is masked to zero
+      orow = -1;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        Q[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+        dOb[kk] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      }
+    }
+  }
+  const float c_log2 = scale * 1.4426950408889634f;
+
+  int koff[KK], ioff[4];
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) koff[kk] = row_operand_offset<D>(l32, hf, kk);
+#pragma unroll
+  for (int ch = 0; ch < 4; ++ch) ioff[ch] = image_operand_offset(l32, hf, ch);
+
+  // tiles 0 .. tp-1 cover the prefix, tp .. tp+ts-1 the rollout's own keys
+  const int tp = (P + TILE - 1) / TILE;
+  const int ts = (nkeys + TILE - 1) / TILE;
+  const int ntiles = tp + ts;
+  const __bf16* kpb = k_prefix + (int64_t)it.c * D;
+  const __bf16* vpb = v_prefix + (int64_t)it.c * D;
+  const __bf16* ksb = k_suffix + ((int64_t)off_g * Hkv + it.c) * D;
+  const __bf16* vsb = v_suffix + ((int64_t)off_g * Hkv + it.c) * D;
+  const __bf16* ktpb = kt_prefix + (int64_t)it.c * tiles_prefix * (D * TILE);
+  const __bf16* ktsb = kt_suffix + ((int64_t)it.c * tiles_suffix + vt_off[it.g]) * (D * TILE);
+
+  auto issue = [&](int u, int buf) {
+    unsigned char* dst = smem + buf * STAGE;
+    const bool pre = u < tp;
+    const int j = pre ? u : u - tp;              // tile index inside its key set
+    const int left = (pre ? P : nkeys) - j * TILE;  // keys of the tile that exist (>= 1)
+    const __bf16* kb = (pre ? kpb : ksb) + (int64_t)j * TILE * row_stride;
+    const __bf16* vb = (pre ? vpb : vsb) + (int64_t)j * TILE * row_stride;
+    issue_row_tile<D, DQ_WAVES>(dst, kb, row_stride, left, wave, lane);
+    issue_row_tile<D, DQ_WAVES>(dst + G::ROW_TILE_BYTES, vb, row_stride, left, wave, lane);
+    issue_linear<G::IMAGE_BYTES, DQ_WAVES>(dst + 2 * G::ROW_TILE_BYTES, (pre ? ktpb : ktsb) + (int64_t)j * (D * TILE),
+                                            wave, lane);
+  };
+
+  f32x16 dQ[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) dQ[db][i] = 0.f;
+
+  issue(0, 0);
+  for (int u = 0; u < ntiles; ++u) {
+    const int buf = u & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile u has landed
+    __syncthreads();                      // everyone's share has; buffer buf^1 is no longer read
+    if (u + 1 < ntiles) issue(u + 1, buf ^ 1);
+    const unsigned char* kt = smem + buf * STAGE;
+    const unsigned char* vt = kt + G::ROW_TILE_BYTES;
+    const unsigned char* im = kt + 2 * G::ROW_TILE_BYTES;
+    const bool pre = u < tp;
+    const int key_tile0 = (pre ? u : u - tp) * TILE;
+    // last visible key index inside this tile's key set, for this lane's query
+    const int limit = pre ? P - 1 : pos;
+    const bool no_mask = pre ? (key_tile0 + TILE <= P) : false;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      f32x16 S, W;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        S[i] = 0.f;
+        W[i] = 0.f;
+      }
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 ka = lds_operand(kt + kb * 32 * G::ROWB + koff[kk]);
+        const bf16x8 va = lds_operand(vt + kb * 32 * G::ROWB + koff[kk]);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, Q[kk], S, 0, 0, 0);
+        W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dOb[kk], W, 0, 0, 0);
+      }
+      // register i: key key_tile0 + kb*32 + 8*(i/4) + 4*hf + i%4
+      bf16x8 dSb[2];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        float ds[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int i = 4 * a + e;
+          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2));
+          const int key = key_tile0 + kb * 32 + 8 * a + 4 * hf + e;
+          if (!no_mask && key > limit) p = 0.f;
+          ds[e] = p * (W[i] - dl);
+        }
+        pack4(ds, 4 * a, dSb);
+      }
+#pragma unroll
+      for (int c2 = 0; c2 < 2; ++c2)
+#pragma unroll
+        for (int db = 0; db < DB; ++db) {
+          const bf16x8 ta = lds_operand(im + db * 32 * 128 + ioff[2 * kb + c2]);
+          dQ[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, dSb[c2], dQ[db], 0, 0, 0);
+        }
+    }
+  }
+
+  // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's query
+  if (orow >= 0) {
+    __bf16* op = dq + orow * D + 4 * hf;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const f32x4 w = {dQ[db][4 * a] * scale, dQ[db][4 * a + 1] * scale, dQ[db][4 * a + 2] * scale,
+                         dQ[db][4 * a + 3] * scale};
+        *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * a) = __builtin_convertvector(w, bf16x4);
+      }
+  }
+}
+
+}  // namespace
+
+int launch_bwd_dq_bf16(const BwdDqArgs& a, void* stream) {
+  if (a.num_items == 0) return 0;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
+  const unsigned grid = (unsigned)a.num_items;
+#define PA_LAUNCH(DD)                                                                                             \
+  bwd_dq_kernel<DD><<<grid, DQ_THREADS, 0, s>>>(b(a.q), b(a.d_out), b(a.k_prefix), b(a.v_prefix), b(a.k_suffix), \
+                                                b(a.v_suffix), b(a.kt_prefix), b(a.kt_suffix), a.lse2s, a.deltas, a.Mpad, \
+                                                static_cast<__bf16*>(a.dq), a.items, a.cu, a.vt_off, (int)a.P,   \
+                                                a.tiles_prefix, a.tiles_suffix, a.Hq, a.Hkv, a.group, a.scale)
+  if (a.D == 128) PA_LAUNCH(128); else PA_LAUNCH(64);
+#undef PA_LAUNCH
+  return (int)hipGetLastError();
+}
+
+}  // namespace pa

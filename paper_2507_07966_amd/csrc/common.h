@@ -27,6 +27,21 @@ struct WorkItem {
   int32_t nkeys;  // keys swept: P in the prefix pass, causal extent in the suffix pass
 };
 
+// Backward tile geometry.  The key-stationary pass (dK/dV) gives a workgroup KEYS_PER_KEY_ITEM
+// keys of one kv head and streams stacked query rows past them in tiles of ROWS_PER_ROW_TILE.
+// Stacked rows of kv head c are numbered over all packed tokens: M = t * group + j.
+constexpr int KEY_WAVES = 4;
+constexpr int KEYS_PER_KEY_ITEM = 32 * KEY_WAVES;
+constexpr int ROWS_PER_ROW_TILE = 64;
+
+// One entry of the dK/dV work list.  c < 0 marks a padding entry (the workgroup exits).
+struct KeyItem {
+  int32_t g;      // -1: prefix keys (seen by every row); otherwise the rollout owning the keys
+  int32_t key0;   // first key of the block (prefix index, or position inside the rollout)
+  int32_t c;      // kv head
+  int32_t nkeys;  // keys in the block (<= KEYS_PER_KEY_ITEM)
+};
+
 // Arguments of one attention pass (prefix or suffix).  All pointers are device pointers.
 struct PassArgs {
   const void* q;        // [T, Hq, D]
@@ -93,4 +108,10 @@ struct prefix_attn_plan {
   pa::WorkItem* d_items[2] = {nullptr, nullptr};
   // workspace layout, byte offsets
   size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;
+  // backward: dK/dV work lists (0 = prefix key blocks, 1 = suffix key blocks) and workspace layout
+  std::vector<pa::KeyItem> key_items[2];
+  pa::KeyItem* d_key_items[2] = {nullptr, nullptr};
+  int64_t Mpad = 0;                    // stacked rows per kv head, rounded up to ROWS_PER_ROW_TILE
+  size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_qst = 0, boff_dost = 0, boff_lse2s = 0, boff_deltas = 0,
+         boff_toks = 0, boff_ktp = 0, boff_kts = 0, bws_bytes = 0;
 };

@@ -1,0 +1,113 @@
+// Building blocks of the bf16 MFMA backward kernels (gfx950): vector types, the two LDS tile
+// layouts with their bank-conflict-free XOR swizzles, direct-to-LDS tile loads and the lane
+// exchange.  Device code only.
+//
+// v_mfma_f32_32x32x16_bf16 operand layout (64 lanes, l32 = lane % 32, hf = lane / 32):
+//   A: lane holds row l32 of the 32-row block, contraction indices 8*hf .. 8*hf+7
+//   B: lane holds column l32,                  contraction indices 8*hf .. 8*hf+7
+//   C: register i holds row 8*(i/4) + 4*hf + i%4, column l32
+// An accumulator of a first product is turned into the B operand of a second product by
+// packing registers 0..7 and 8..15 into two 8-element operands; contraction slot e of half hf
+// then is accumulator row 4*hf + e (e < 4) or 8 + 4*hf + (e - 4) of the 16-row chunk, i.e. the
+// rows of a chunk appear in the order 0-3, 8-11, 4-7, 12-15.  The transposed tile images store
+// their 64 columns in exactly this order, so the second product's A operand matches.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace pa {
+namespace mt {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+#define PA_LDS_PTR(T) __attribute__((address_space(3))) T*
+#define PA_GLB_PTR(T) __attribute__((address_space(1))) T*
+
+constexpr int TILE = 64;  // rows of a row-major tile = columns of a transposed image
+
+// Row-major tile: 64 rows of D bf16 (rows of 2*D bytes).  Transposed image: D rows of 64 bf16
+// (rows of 128 bytes).  The 16-byte chunk j of row r is stored at chunk position
+//   j ^ (r & 15)         for 256-byte rows,
+//   j ^ ((r >> 1) & 7)   for 128-byte rows,
+// so 16 consecutive rows read at one logical chunk cover all 64 banks.
+__device__ inline int swizzle_term(int row, int rowb) { return rowb == 256 ? (row & 15) : ((row >> 1) & 7); }
+
+template <int D>
+struct Geo {
+  static constexpr int ROWB = D * 2;            // bytes per row of a row-major tile
+  static constexpr int ROW_TILE_BYTES = TILE * ROWB;
+  static constexpr int IMAGE_BYTES = D * 128;
+  static constexpr int KK = D / 16;             // contraction steps over the head dimension
+  static constexpr int DB = D / 32;             // 32-channel blocks
+};
+
+// Byte offset, inside a row-major tile, of the A/B operand of row (blk*32 + l32) and channels
+// 16*kk + 8*hf .. +7.  (Rows blk*32.. share the swizzle of rows 0..31 because 32 % 16 == 0.)
+template <int D>
+__device__ inline int row_operand_offset(int l32, int hf, int kk) {
+  return l32 * Geo<D>::ROWB + (((2 * kk + hf) ^ swizzle_term(l32, Geo<D>::ROWB)) << 4);
+}
+// Byte offset, inside a transposed image, of the A operand of channel (db*32 + l32) and the
+// 16-column chunk ch (contraction slots 8*hf .. 8*hf+7 of that chunk).
+__device__ inline int image_operand_offset(int l32, int hf, int ch) {
+  return l32 * 128 + (((2 * ch + hf) ^ swizzle_term(l32, 128)) << 4);
+}
+
+__device__ inline bf16x8 lds_operand(const unsigned char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// Direct-to-LDS copy of 1 KiB per wavefront-wide instruction: lane l's 16 bytes land at dst + 16*l.
+__device__ inline void load16_to_lds(const void* src, unsigned char* dst) {
+  __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))src, (PA_LDS_PTR(void))dst, 16, 0, 0);
+}
+
+// Row-major tile -> LDS, NW wavefronts cooperating.  `first` points at channel 0 of the tile's
+// first row, rows are row_stride elements apart, rows at or past `rows_left` repeat the last
+// existing row (callers mask what those rows produce).  rows_left >= 1.
+template <int D, int NW>
+__device__ inline void issue_row_tile(unsigned char* dst, const __bf16* first, int64_t row_stride, int rows_left,
+                                      int wave, int lane) {
+  constexpr int ROWB = Geo<D>::ROWB;
+  constexpr int BLOCKS_PER_WAVE = Geo<D>::ROW_TILE_BYTES / 1024 / NW;
+  constexpr int LANES_PER_ROW = ROWB / 16, ROWS_PER_BLOCK = 1024 / ROWB;
+  static_assert(BLOCKS_PER_WAVE >= 1, "every wavefront copies at least one block");
+#pragma unroll
+  for (int n = 0; n < BLOCKS_PER_WAVE; ++n) {
+    const int blk = wave * BLOCKS_PER_WAVE + n;
+    int row = blk * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
+    const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, ROWB)) * 8;  // logical chunk stored at this position
+    row = row < rows_left ? row : rows_left - 1;
+    load16_to_lds(first + row * row_stride + col, dst + blk * 1024);
+  }
+}
+
+// Linear copy of `bytes` (a multiple of 1024 * NW) global -> LDS.
+template <int BYTES, int NW>
+__device__ inline void issue_linear(unsigned char* dst, const void* src, int wave, int lane) {
+  constexpr int BLOCKS_PER_WAVE = BYTES / 1024 / NW;
+  static_assert(BLOCKS_PER_WAVE >= 1 && BYTES % (1024 * NW) == 0, "whole blocks per wavefront");
+  const char* s = static_cast<const char*>(src) + (wave * BLOCKS_PER_WAVE) * 1024 + lane * 16;
+#pragma unroll
+  for (int n = 0; n < BLOCKS_PER_WAVE; ++n) load16_to_lds(s + n * 1024, dst + (wave * BLOCKS_PER_WAVE + n) * 1024);
+}
+
+// Pack four fp32 accumulator registers [r0, r0+4) of a 16-register block into the B operand
+// pair Pb[2]: register r goes to operand r >> 3, slot r & 7.
+__device__ inline void pack4(const float (&x)[4], int r0, bf16x8 (&Pb)[2]) {
+  const f32x2 a = {x[0], x[1]}, b = {x[2], x[3]};
+  const bf16x2 pa = __builtin_convertvector(a, bf16x2), pb = __builtin_convertvector(b, bf16x2);
+  Pb[r0 >> 3][(r0 & 7) + 0] = pa[0];
+  Pb[r0 >> 3][(r0 & 7) + 1] = pa[1];
+  Pb[r0 >> 3][(r0 & 7) + 2] = pb[0];
+  Pb[r0 >> 3][(r0 & 7) + 3] = pb[1];
+}
+
+}  // namespace mt
+}  // namespace pa

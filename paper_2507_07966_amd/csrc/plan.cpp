@@ -86,6 +86,72 @@ void build_suffix_items(prefix_attn_plan_t& p) {
   std::stable_sort(out.begin(), out.end(), [](const WorkItem& a, const WorkItem& b) { return a.nkeys > b.nkeys; });
 }
 
+// Backward, dK/dV pass: one item per block of KEYS_PER_KEY_ITEM keys of a kv head.  A prefix
+// block streams the stacked rows of every rollout, all blocks of a kv head in the same order,
+// so (as in the prefix pass) one kv head's blocks are kept on a fixed subset of XCDs and share
+// the streamed Q/dO tiles through that subset's L2.  A suffix block streams the rollout's rows
+// from its first key on; longest first.
+void build_key_items(prefix_attn_plan_t& p) {
+  const int Hkv = p.desc.num_kv_heads;
+  const int P = (int)p.desc.prefix_len;
+  const int KB = pa::KEYS_PER_KEY_ITEM;
+  std::vector<pa::KeyItem>& pre = p.key_items[0];
+  pre.clear();
+  if (P > 0) {
+    std::vector<std::vector<pa::KeyItem>> per_head(Hkv);
+    for (int c = 0; c < Hkv; ++c)
+      for (int key0 = 0; key0 < P; key0 += KB) per_head[c].push_back({-1, key0, c, std::min(KB, P - key0)});
+    const size_t per = per_head[0].size();
+    if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
+      const int xper = pa::NUM_XCD / Hkv;
+      const size_t qlen = (per + xper - 1) / xper;
+      pre.assign(qlen * pa::NUM_XCD, pa::KeyItem{-1, 0, -1, 0});
+      for (int x = 0; x < pa::NUM_XCD; ++x) {
+        const int c = x / xper, sub = x % xper;
+        for (size_t k = 0; k * xper + sub < per; ++k) pre[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
+      }
+    } else {
+      for (int c = 0; c < Hkv; ++c) pre.insert(pre.end(), per_head[c].begin(), per_head[c].end());
+    }
+  }
+  std::vector<pa::KeyItem>& suf = p.key_items[1];
+  suf.clear();
+  for (int c = 0; c < Hkv; ++c)
+    for (int g = 0; g < p.desc.num_rollouts; ++g)
+      for (int key0 = 0; key0 < p.lens[g]; key0 += KB) suf.push_back({g, key0, c, std::min(KB, p.lens[g] - key0)});
+  const std::vector<int32_t>& lens = p.lens;
+  std::stable_sort(suf.begin(), suf.end(), [&lens](const pa::KeyItem& a, const pa::KeyItem& b) {
+    return lens[a.g] - a.key0 > lens[b.g] - b.key0;
+  });
+}
+
+// Backward workspace: delta and the re-ordered LSE (used by the fp32 path); for bf16 also the stacked Q/dO copies, their
+// transposed images, the per-row statistics and the transposed K images.
+void layout_backward_workspace(prefix_attn_plan_t& p) {
+  const prefix_attn_desc_t& d = p.desc;
+  const size_t rows = (size_t)p.T * d.num_q_heads;
+  p.Mpad = ((int64_t)p.T * p.group + pa::ROWS_PER_ROW_TILE - 1) / pa::ROWS_PER_ROW_TILE * pa::ROWS_PER_ROW_TILE;
+  p.boff_delta = 0;
+  p.boff_lse_th = align_up(rows * sizeof(float), 256);
+  size_t end = 2 * p.boff_lse_th;
+  if (d.dtype == PA_BF16) {
+    const size_t stacked = align_up((size_t)d.num_kv_heads * p.Mpad * d.head_dim * 2, 256);
+    const size_t stats = align_up((size_t)d.num_kv_heads * p.Mpad * 4, 256);
+    const size_t image = (size_t)d.head_dim * pa::KEYS_PER_TILE * 2;
+    p.boff_qs = end;
+    p.boff_dos = p.boff_qs + stacked;
+    p.boff_qst = p.boff_dos + stacked;
+    p.boff_dost = p.boff_qst + stacked;
+    p.boff_lse2s = p.boff_dost + stacked;
+    p.boff_deltas = p.boff_lse2s + stats;
+    p.boff_toks = p.boff_deltas + stats;
+    p.boff_ktp = p.boff_toks + stats;
+    p.boff_kts = p.boff_ktp + align_up((size_t)d.num_kv_heads * p.tiles_prefix * image, 256);
+    end = p.boff_kts + align_up((size_t)d.num_kv_heads * p.tiles_suffix * image, 256);
+  }
+  p.bws_bytes = end;
+}
+
 }  // namespace
 
 extern "C" {
@@ -112,6 +178,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     p->group = desc->num_q_heads / desc->num_kv_heads;
     build_prefix_items(*p);
     build_suffix_items(*p);
+    build_key_items(*p);
   } catch (const std::bad_alloc&) {
     delete p;
     return PA_ERR_ALLOC;
@@ -132,6 +199,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     end = p->off_vts + align_up((size_t)desc->num_kv_heads * p->tiles_suffix * image, 256);
   }
   p->ws_bytes = end;
+  layout_backward_workspace(*p);
 
   if (desc->device >= 0) {
     int prev = 0;
@@ -147,6 +215,12 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
         const size_t bytes = p->items[s].size() * sizeof(WorkItem);
         ok = hipMalloc((void**)&p->d_items[s], bytes) == hipSuccess &&
              hipMemcpy(p->d_items[s], p->items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+      }
+      for (int s = 0; ok && s < 2; ++s) {
+        if (p->key_items[s].empty()) continue;
+        const size_t bytes = p->key_items[s].size() * sizeof(pa::KeyItem);
+        ok = hipMalloc((void**)&p->d_key_items[s], bytes) == hipSuccess &&
+             hipMemcpy(p->d_key_items[s], p->key_items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
       }
       (void)hipSetDevice(prev);
     }
@@ -166,6 +240,8 @@ void prefix_attn_destroy(prefix_attn_plan_t* plan) {
   if (plan->d_cu) (void)hipFree(plan->d_cu);
   for (int s = 0; s < 2; ++s)
     if (plan->d_items[s]) (void)hipFree(plan->d_items[s]);
+  for (int s = 0; s < 2; ++s)
+    if (plan->d_key_items[s]) (void)hipFree(plan->d_key_items[s]);
   delete plan;
 }
 
@@ -209,5 +285,29 @@ int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t
 }
 
 int64_t prefix_attn_plan_total_tokens(const prefix_attn_plan_t* plan) { return plan ? plan->T : -1; }
+
+int prefix_attn_backward_workspace(const prefix_attn_plan_t* plan, size_t* workspace_bytes_out) {
+  if (!plan || !workspace_bytes_out) return PA_ERR_NULL;
+  *workspace_bytes_out = plan->bws_bytes;
+  return PA_OK;
+}
+
+int64_t prefix_attn_plan_num_key_items(const prefix_attn_plan_t* plan, int32_t pass) {
+  if (!plan || pass < 0 || pass > 1) return -1;
+  return (int64_t)plan->key_items[pass].size();
+}
+
+int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out) {
+  if (!plan || !items_out) return PA_ERR_NULL;
+  if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
+  const std::vector<pa::KeyItem>& v = plan->key_items[pass];
+  for (size_t n = 0; n < v.size(); ++n) {
+    items_out[4 * n + 0] = v[n].g;
+    items_out[4 * n + 1] = v[n].key0;
+    items_out[4 * n + 2] = v[n].c;
+    items_out[4 * n + 3] = v[n].nkeys;
+  }
+  return PA_OK;
+}
 
 }  // extern "C"

@@ -151,6 +151,17 @@ def make_custom(dtype, Hq, Hkv, D, P, suffix_lens, seed=0, name="custom", std=1.
                   vals["v_suffix"], bits)
 
 
+def make_d_out(x: Inputs, seed: int = 1):
+    """Upstream gradient dL/d(out) for the backward: iid N(0,1) of the shape of q, rounded to bf16 for
+    bf16 workloads.  Returns (fp32 values both sides consume, uint16 bit patterns or None)."""
+    rng = np.random.default_rng(1000003 * (x.workload.seed + 1) + seed)
+    raw = rng.standard_normal(x.q.shape, dtype=np.float32)
+    if x.workload.dtype == "bf16":
+        bits, vals = round_to_bf16(raw)
+        return vals, bits
+    return raw, None
+
+
 # ---------------------------------------------------------------- accounting (measurement only)
 
 def visible_pairs(prefix_len: int, suffix_lens) -> int:
@@ -161,6 +172,12 @@ def visible_pairs(prefix_len: int, suffix_lens) -> int:
 def effective_flop(Hq: int, D: int, prefix_len: int, suffix_lens) -> int:
     """4 D FLOP per visible pair (2D for QK^T, 2D for PV), all q-heads."""
     return 4 * D * Hq * visible_pairs(prefix_len, suffix_lens)
+
+
+def backward_flop(Hq: int, D: int, prefix_len: int, suffix_lens) -> int:
+    """10 D FLOP per visible pair: the five products S = QK^T, dW = dO V^T, dV += W^T dO, dK += dS^T Q and
+    dQ += dS K, counted once each (recomputation of S and dW in the second pass is not counted)."""
+    return 10 * D * Hq * visible_pairs(prefix_len, suffix_lens)
 
 
 def algorithmic_bytes(w: Workload, suffix_lens) -> int:

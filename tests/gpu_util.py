@@ -52,3 +52,70 @@ def check(out, lse, ref_out, ref_lse, label=""):
     assert d.mean() <= OUT_MEAN_ABS, msg
     assert dl.max() <= LSE_MAX_ABS, msg
     return d.max(), d.mean(), dl.max()
+
+
+GRAD_NAMES = ("dq", "dk_prefix", "dv_prefix", "dk_suffix", "dv_suffix")
+# Gradient tolerances.  An element may be off by
+#   |err| <= GRAD_REL * |ref| + GRAD_ABS_RMS * rms(ref),   and   mean|err| <= GRAD_MEAN_RMS * rms(ref).
+# bf16 path: (1) every gradient is rounded to bf16 once at the end: relative 2^-9 of the element
+# (GRAD_REL leaves a factor 2); (2) the weights W and dS are rounded to bf16 before the two
+# accumulating products: independent relative 2^-9 errors, a few 1e-3 of the tensor's rms after
+# summation; (3) delta = <dO, O> is taken from the bf16-rounded forward output, which perturbs
+# every dS of a row by W * (2^-9-level error of a length-D dot product); it matters for rows that
+# see only a few keys, where it reaches a few percent of the tensor's rms.  The mean bound is the
+# sharp one (an ideal rounding of the exact gradient alone gives about 1.1e-3 rms).
+GRAD_REL = {"bf16": 2.0 ** -8, "f32": 1e-5}
+GRAD_ABS_RMS = {"bf16": 8e-2, "f32": 1e-4}
+GRAD_MEAN_RMS = {"bf16": 3e-3, "f32": 1e-5}
+
+
+def run_hip_backward(x, d_out, d_out_bits=None, scale=None, keep=False):
+    """forward + backward through the C ABI.  Returns a dict name -> float64 array (and the forward out)."""
+    import torch
+    import paper_2507_07966_amd as pa
+    w = x.workload
+    scale = w.scale if scale is None else scale
+    out64, lse64, plan, dev, ws, out, lse = run_hip(x, scale, return_plan=True)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    if w.dtype == "bf16":
+        do = torch.from_numpy(d_out_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        do = torch.from_numpy(d_out).cuda()
+    T, P = x.total_suffix, w.prefix_len
+    nan = float("nan")
+    g = {"dq": torch.full((T, w.num_q_heads, w.head_dim), nan, dtype=tdt, device="cuda"),
+         "dk_prefix": torch.full((P, w.num_kv_heads, w.head_dim), nan, dtype=tdt, device="cuda"),
+         "dv_prefix": torch.full((P, w.num_kv_heads, w.head_dim), nan, dtype=tdt, device="cuda"),
+         "dk_suffix": torch.full((T, w.num_kv_heads, w.head_dim), nan, dtype=tdt, device="cuda"),
+         "dv_suffix": torch.full((T, w.num_kv_heads, w.head_dim), nan, dtype=tdt, device="cuda")}
+    bws = torch.empty(max(plan.backward_workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    has_p = P > 0
+    args = (plan, dev["q"], dev["k_prefix"] if has_p else None, dev["v_prefix"] if has_p else None, dev["k_suffix"],
+            dev["v_suffix"], out, do, lse, g["dq"], g["dk_prefix"] if has_p else None, g["dv_prefix"] if has_p else None,
+            g["dk_suffix"], g["dv_suffix"], bws)
+    pa.prefix_attn_backward(*args)
+    torch.cuda.synchronize()
+    res = {n: t.float().cpu().numpy().astype(np.float64) for n, t in g.items()}
+    if keep:
+        return res, (plan, args, g)
+    plan.destroy()
+    return res
+
+
+def check_grads(got, ref, dtype, label=""):
+    """got: dict from run_hip_backward; ref: the oracle's five arrays in GRAD_NAMES order."""
+    worst = 0.0
+    for n, r in zip(GRAD_NAMES, ref):
+        a = got[n]
+        assert a.shape == r.shape, f"{label} {n}: shape {a.shape} vs {r.shape}"
+        if r.size == 0:
+            continue
+        assert np.isfinite(a).all(), f"{label} {n}: non-finite gradient"
+        rms = float(np.sqrt(np.mean(r * r)))
+        d = np.abs(a - r)
+        msg = f"{label} {n}: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (reference rms {rms:.3e})"
+        print(msg, flush=True)
+        assert (d <= GRAD_REL[dtype] * np.abs(r) + GRAD_ABS_RMS[dtype] * rms + 1e-30).all(), msg
+        assert d.mean() <= GRAD_MEAN_RMS[dtype] * rms + 1e-30, msg
+        worst = max(worst, d.max() / max(rms, 1e-30))
+    return worst
