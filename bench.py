@@ -5,6 +5,7 @@ One "step" = one pass of the whole hot path (prefix pass + suffix pass + merge +
 over one synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C3] [--no-cpu-baseline]
+  python bench.py --direction backward ...   times prefix_attn_backward instead (see backward_main)
 
 metric  : effective attention TFLOP/s = 4 D Hq sum_g[S_g P + S_g (S_g + 1) / 2] / time
 roofline: the prefix pass (the dominant kernel) against the published dense bf16 MFMA peak
@@ -47,6 +48,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C3")
+    ap.add_argument("--direction", choices=("forward", "backward"), default="forward",
+                    help="forward (default): the prefill attention hot path; backward: its gradient pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -90,6 +93,10 @@ def main():
     def step():
         pa.prefix_attn_forward(*fwd_args)
         pa.prefix_attn_lse(plan, ws, lse)
+
+    if args.direction == "backward":
+        step()
+        return backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse)
 
     for _ in range(args.warmup):
         step()
@@ -195,6 +202,95 @@ def main():
         result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - o_ref).max()),
                                       "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
                                       "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
+    print(json.dumps(result), flush=True)
+
+
+def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
+    """One "step" = one prefix_attn_backward call (pre-pass, dQ pass, dK/dV passes) on the outputs of a
+    forward call, everything resident in HBM.  metric: 10 D Hq pairs / time (five products, each once)."""
+    T, P = x.total_suffix, w.prefix_len
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    do_vals, do_bits = wl.make_d_out(x)
+    if w.dtype == "bf16":
+        do = torch.from_numpy(do_bits.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        do = torch.from_numpy(do_vals).cuda()
+    g = {"dq": torch.empty((T, w.num_q_heads, w.head_dim), dtype=tdt, device="cuda"),
+         "dk_prefix": torch.empty((P, w.num_kv_heads, w.head_dim), dtype=tdt, device="cuda"),
+         "dv_prefix": torch.empty((P, w.num_kv_heads, w.head_dim), dtype=tdt, device="cuda"),
+         "dk_suffix": torch.empty((T, w.num_kv_heads, w.head_dim), dtype=tdt, device="cuda"),
+         "dv_suffix": torch.empty((T, w.num_kv_heads, w.head_dim), dtype=tdt, device="cuda")}
+    bws = torch.empty(max(plan.backward_workspace_bytes, 16), dtype=torch.uint8, device="cuda")
+    has_p = P > 0
+    bargs = (plan, dev["q"], dev["k_prefix"] if has_p else None, dev["v_prefix"] if has_p else None, dev["k_suffix"],
+             dev["v_suffix"], out, do, lse, g["dq"], g["dk_prefix"] if has_p else None,
+             g["dv_prefix"] if has_p else None, g["dk_suffix"], g["dv_suffix"], bws)
+    for _ in range(args.warmup):
+        pa.prefix_attn_backward(*bargs)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        pa.prefix_attn_backward(*bargs)
+    e1.record()
+    torch.cuda.synchronize()
+    ms_per_step = float(e0.elapsed_time(e1) / args.steps)
+    kms = np.array([pa.prefix_attn_backward_timed(*bargs) for _ in range(args.steps)]).mean(axis=0)
+    pairs = wl.visible_pairs(P, x.suffix_lens)
+    flop = wl.backward_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
+    tflops = flop / (ms_per_step * 1e-3) * 1e-12
+    # dominant kernel: the dK/dV pass over the prefix keys executes four products (S, dW, dV, dK) per pair
+    if has_p:
+        dom_name, dom_flop, dom_ms = "bwd_dkv_prefix", 8 * w.head_dim * w.num_q_heads * T * P, float(kms[2])
+    else:
+        dom_name, dom_flop, dom_ms = "bwd_dkv_suffix", 8 * w.head_dim * w.num_q_heads * pairs, float(kms[3])
+    achieved = dom_flop / (dom_ms * 1e-3) * 1e-12
+    result = {
+        "metric": "effective attention backward TFLOP/s", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name} backward: {w.note}", "num_q_heads": w.num_q_heads,
+                   "num_kv_heads": w.num_kv_heads, "head_dim": w.head_dim, "prefix_len": P,
+                   "num_rollouts": w.num_rollouts, "total_suffix_tokens": T},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "effective_flop": flop,
+        "kernel_ms": {"prepass": round(float(kms[0]), 4), "dq": round(float(kms[1]), 4),
+                      "dkv_prefix": round(float(kms[2]), 4), "dkv_suffix": round(float(kms[3]), 4)},
+        "executed_mfma_tflops": {"dq": round(6 * w.head_dim * w.num_q_heads * pairs / (kms[1] * 1e-3) * 1e-12, 1)},
+        "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic(w.name, dom_name)},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import cref
+        rows_all = wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 96, seed=1)
+        rng = np.random.default_rng(2)
+        rng.shuffle(rows_all)
+
+        def run_oracle(rows):
+            t = time.perf_counter()
+            dq_ref, thr = cref.prefix_shared_attention_backward(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
+                                                                x.suffix_lens, w.scale, do_vals, rows=rows)
+            return dq_ref, thr, time.perf_counter() - t
+
+        off = np.concatenate([[0], np.cumsum(x.suffix_lens.astype(np.int64))])
+        run_oracle(rows_all[:1])
+        probe = rows_all[:16]
+        _, thr, t_probe = run_oracle(probe)
+        n = int(max(16, min(len(rows_all), args.cpu_seconds / max(t_probe / len(probe), 1e-6))))
+        rows = np.sort(rows_all[:n])
+        dq_ref, thr, t_cpu = run_oracle(rows)
+        gi = np.searchsorted(off, rows, side="right") - 1
+        cpu_pairs = int(np.sum(P + (rows - off[gi]) + 1))
+        cpu_flop = 6 * w.head_dim * w.num_q_heads * cpu_pairs     # the oracle's dQ rows: S, dW and dQ products
+        dq_gpu = g["dq"][torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        rms = float(np.sqrt(np.mean(dq_ref * dq_ref)))
+        result["cpu_baseline"] = {
+            "value": round(cpu_flop / t_cpu * 1e-12, 6), "unit": "TFLOP/s", "cores": int(thr), "kind": "oracle",
+            "sample": f"dQ of {len(rows)} seeded query rows x {w.num_q_heads} heads of {w.name} against their full key "
+                      f"sets (fp64, {t_cpu:.1f} s)", "seconds": round(t_cpu, 2)}
+        result["parity_on_sample"] = {"dq_max_abs_over_rms": float(np.abs(dq_gpu - dq_ref).max() / rms),
+                                      "dq_mean_abs_over_rms": float(np.abs(dq_gpu - dq_ref).mean() / rms)}
     print(json.dumps(result), flush=True)
 
 

@@ -13,8 +13,9 @@
 //   dK^T += Q^T dS               (A = transposed Q image,  B = dS packed to bf16)
 // The stacked, row-major Q/dO copies and their transposed images come from the pre-pass; a
 // tile (4 x 16 KiB + statistics) goes global -> LDS with direct-to-LDS loads, double buffered,
-// one barrier per tile.  One wavefront per SIMD: the accumulators (128 registers) and the K/V
-// columns (64) need more than half of the register file.
+// one barrier per tile.  One wavefront per SIMD (the accumulators, 128 registers, and the K/V
+// columns, 64, need more than half of the register file), so the overlap of MFMA and VALU work
+// is arranged inside the wavefront: see the step stream in the kernel.
 #include <hip/hip_runtime.h>
 
 #include "bwd.h"
@@ -93,21 +94,27 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   const unsigned tkey = (unsigned)(off_g + key);
   const unsigned tspan = (unsigned)(end_g - (off_g + key));
 
-  auto issue = [&](int tile, int buf) {
+  // The loads of a tile are issued in four pieces so they can be spread over the MFMA stream.
+  auto issue_piece = [&](int tile, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
     const int64_t e0 = (int64_t)tile * TILE * D;  // first element of the tile in each of the four arrays
-    if (wave == 0) {  // per-row statistics: 64 dwords each, lane l's word lands at word l
-      unsigned char* st = dst + 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES;
-      const int64_t m = (int64_t)tile * TILE + lane;
-      __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(lse_c + m), (PA_LDS_PTR(void))st, 4, 0, 0);
-      __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(del_c + m), (PA_LDS_PTR(void))(st + TILE * 4), 4, 0, 0);
-      if (CAUSAL)
-        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(tok_c + m), (PA_LDS_PTR(void))(st + 2 * TILE * 4), 4, 0, 0);
+    if (piece == 0) {
+      if (wave == 0) {  // per-row statistics: 64 dwords each, lane l's word lands at word l
+        unsigned char* st = dst + 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES;
+        const int64_t m = (int64_t)tile * TILE + lane;
+        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(lse_c + m), (PA_LDS_PTR(void))st, 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(del_c + m), (PA_LDS_PTR(void))(st + TILE * 4), 4, 0, 0);
+        if (CAUSAL)
+          __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(tok_c + m), (PA_LDS_PTR(void))(st + 2 * TILE * 4), 4, 0, 0);
+      }
+      issue_row_tile<D, KEY_WAVES>(dst, qs_c + e0, D, TILE, wave, lane);
+    } else if (piece == 1) {
+      issue_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, D, TILE, wave, lane);
+    } else if (piece == 2) {
+      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, qst_c + e0, wave, lane);
+    } else {
+      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, dost_c + e0, wave, lane);
     }
-    issue_row_tile<D, KEY_WAVES>(dst, qs_c + e0, D, TILE, wave, lane);
-    issue_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, D, TILE, wave, lane);
-    issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, qst_c + e0, wave, lane);
-    issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, dost_c + e0, wave, lane);
   };
 
   f32x16 dK[DB], dV[DB];
@@ -119,61 +126,108 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
       dV[db][i] = 0.f;
     }
 
-  if (tile0 < tile1) issue(tile0, 0);
+  // One tile = a stream of NS steps of two MFMAs each, operands read from LDS PF steps ahead:
+  //   steps [0, 2KK):       S[rb] += Q_rb K^T,  dW[rb] += dO_rb V^T        (rb = step / KK)
+  //   steps [2KK, 2KK+4DB): dV += dO^T W,  dK += Q^T dS, 16-row chunk by chunk (block, chunk, channel block)
+  // The VALU work that turns (S, dW) of a 32-row block into the bf16 operands (W, dS) is cut into
+  // four slices per block and interleaved with the MFMAs of later steps, so both pipes stay busy
+  // although only one wavefront runs per SIMD.
+  constexpr int NSW = 2 * KK, NDK = 4 * DB, NS = NSW + NDK, PF = 2;
+  static_assert(KK % 4 == 0 || KK == 4, "slice schedule assumes KK in {4, 8}");
+  constexpr int SLICE_STRIDE = KK / 4;
+
+  if (tile0 < tile1) {
+#pragma unroll
+    for (int piece = 0; piece < 4; ++piece) issue_piece(tile0, 0, piece);
+  }
   for (int tile = tile0; tile < tile1; ++tile) {
     const int buf = (tile - tile0) & 1;
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+      asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));  // keeps the accumulators in accumulation registers: without
+                                                      // it the allocator parks some in VGPRs and copies them back
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS loads of this wavefront have landed
     __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
-    if (tile + 1 < tile1) issue(tile + 1, buf ^ 1);
+    // the tile after the last one is the last one again: a harmless reload into the idle buffer,
+    // which keeps the step stream free of branches
+    const int next_tile = tile + 1 < tile1 ? tile + 1 : tile;
     const unsigned char* qt = smem + buf * STAGE;
     const unsigned char* dt = qt + G::ROW_TILE_BYTES;
     const unsigned char* qim = qt + 2 * G::ROW_TILE_BYTES;
     const unsigned char* dim = qim + G::IMAGE_BYTES;
     const float* st = reinterpret_cast<const float*>(dim + G::IMAGE_BYTES);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      f32x16 S, W;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        S[i] = 0.f;
-        W[i] = 0.f;
+
+    f32x16 S[2], W[2];
+    bf16x8 Pb[2][2], dSb[2][2];
+    f32x4 l4[2][4], d4[2][4];  // per-slice statistics, each loaded one slice slot before its use
+    i32x4 p4[2][4];
+    bf16x8 op0[NS], op1[NS];  // operand pair of each step (only PF+1 of them are live at a time)
+
+    auto fetch = [&](int s) {
+      if (s < NSW) {
+        const int rb = s / KK, kk = s % KK;
+        op0[s] = lds_operand(qt + rb * 32 * G::ROWB + roff[kk]);
+        op1[s] = lds_operand(dt + rb * 32 * G::ROWB + roff[kk]);
+      } else {
+        const int u = s - NSW, blk = u / (2 * DB), c2 = (u / DB) % 2, db = u % DB;
+        op0[s] = lds_operand(dim + db * 32 * 128 + ioff[2 * blk + c2]);
+        op1[s] = lds_operand(qim + db * 32 * 128 + ioff[2 * blk + c2]);
       }
+    };
+    auto load_stats = [&](int rb, int a) {
+      const int r0 = rb * 32 + 8 * a + 4 * hf;
+      l4[rb][a] = *reinterpret_cast<const f32x4*>(st + r0);
+      d4[rb][a] = *reinterpret_cast<const f32x4*>(st + TILE + r0);
+      if (CAUSAL) p4[rb][a] = *reinterpret_cast<const i32x4*>(st + 2 * TILE + r0);
+    };
+    // slice a of block rb: registers [4a, 4a+4) = rows rb*32 + 8a + 4hf + (0..3) of the tile, this lane's key
+    auto slice = [&](int rb, int a) {
+      float p[4], ds[4];
 #pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 qa = lds_operand(qt + rb * 32 * G::ROWB + roff[kk]);
-        const bf16x8 da = lds_operand(dt + rb * 32 * G::ROWB + roff[kk]);
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, Kb[kk], S, 0, 0, 0);
-        W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, Vb[kk], W, 0, 0, 0);
+      for (int e = 0; e < 4; ++e) {
+        const int i = 4 * a + e;
+        p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[rb][i], c_log2, -l4[rb][a][e]));
+        if (CAUSAL && (unsigned)p4[rb][a][e] - tkey >= tspan) p[e] = 0.f;
+        ds[e] = p[e] * (W[rb][i] - d4[rb][a][e]);
       }
-      // register i: row rb*32 + 8*(i/4) + 4*hf + i%4 of the tile, this lane's key
-      bf16x8 Pb[2], dSb[2];
+      pack4(p, 4 * a, Pb[rb]);
+      pack4(ds, 4 * a, dSb[rb]);
+    };
+
+#pragma unroll
+    for (int s = 0; s < PF; ++s) fetch(s);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      if (s + PF < NS) fetch(s + PF);
+      if (s < NSW) {
+        const int rb = s / KK, kk = s % KK;
+        if (kk == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Kb[kk], zero, 0, 0, 0);
+          W[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], Vb[kk], zero, 0, 0, 0);
+        } else {
+          S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Kb[kk], S[rb], 0, 0, 0);
+          W[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], Vb[kk], W[rb], 0, 0, 0);
+        }
+      } else {
+        const int u = s - NSW, blk = u / (2 * DB), c2 = (u / DB) % 2, db = u % DB;
+        dV[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Pb[blk][c2], dV[db], 0, 0, 0);
+        dK[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dSb[blk][c2], dK[db], 0, 0, 0);
+      }
+      // next tile's loads, one piece after each of the first odd steps
+      if ((s & 1) && s < 8) issue_piece(next_tile, buf ^ 1, s >> 1);
+      __builtin_amdgcn_sched_barrier(0);  // MFMAs first, the VALU slice then runs in their shadow
+      // softmax slices: block 0 after S[0], dW[0] are complete, block 1 after S[1], dW[1]; the
+      // statistics of a slice are read one slot earlier
 #pragma unroll
       for (int a = 0; a < 4; ++a) {
-        const int r0 = rb * 32 + 8 * a + 4 * hf;
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st + r0);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(st + TILE + r0);
-        i32x4 p4 = {0, 0, 0, 0};
-        if (CAUSAL) p4 = *reinterpret_cast<const i32x4*>(st + 2 * TILE + r0);
-        float p[4], ds[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * a + e;
-          p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -l4[e]));
-          if (CAUSAL && (unsigned)p4[e] - tkey >= tspan) p[e] = 0.f;
-          ds[e] = p[e] * (W[i] - d4[e]);
-        }
-        pack4(p, 4 * a, Pb);
-        pack4(ds, 4 * a, dSb);
+        if (s == KK + (a - 1) * SLICE_STRIDE) load_stats(0, a);
+        if (s == 2 * KK + (a - 1) * SLICE_STRIDE) load_stats(1, a);
+        if (s == KK + a * SLICE_STRIDE) slice(0, a);
+        if (s == 2 * KK + a * SLICE_STRIDE) slice(1, a);
       }
-#pragma unroll
-      for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 da = lds_operand(dim + db * 32 * 128 + ioff[2 * rb + c2]);
-          const bf16x8 qa = lds_operand(qim + db * 32 * 128 + ioff[2 * rb + c2]);
-          dV[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(da, Pb[c2], dV[db], 0, 0, 0);
-          dK[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qa, dSb[c2], dK[db], 0, 0, 0);
-        }
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
