@@ -95,6 +95,8 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   const unsigned tspan = (unsigned)(end_g - (off_g + key));
 
   // The loads of a tile are issued in four pieces so they can be spread over the MFMA stream.
+  RowTileOffsets<D, KEY_WAVES> lane_off;
+  lane_off.init(D, wave, lane);
   auto issue_piece = [&](int tile, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
     const int64_t e0 = (int64_t)tile * TILE * D;  // first element of the tile in each of the four arrays
@@ -107,9 +109,9 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         if (CAUSAL)
           __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(tok_c + m), (PA_LDS_PTR(void))(st + 2 * TILE * 4), 4, 0, 0);
       }
-      issue_row_tile<D, KEY_WAVES>(dst, qs_c + e0, D, TILE, wave, lane);
+      issue_full_row_tile<D, KEY_WAVES>(dst, qs_c + e0, lane_off, wave);
     } else if (piece == 1) {
-      issue_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, D, TILE, wave, lane);
+      issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, lane_off, wave);
     } else if (piece == 2) {
       issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, qst_c + e0, wave, lane);
     } else {

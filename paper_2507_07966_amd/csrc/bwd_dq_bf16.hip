@@ -98,17 +98,24 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   const __bf16* ktpb = kt_prefix + (int64_t)it.c * tiles_prefix * (D * TILE);
   const __bf16* ktsb = kt_suffix + ((int64_t)it.c * tiles_suffix + vt_off[it.g]) * (D * TILE);
 
-  auto issue = [&](int u, int buf) {
+  // The loads of a tile are issued in three pieces so they can be spread over the MFMA stream.
+  RowTileOffsets<D, DQ_WAVES> lane_off;
+  lane_off.init(row_stride, wave, lane);
+  auto issue_piece = [&](int u, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
     const bool pre = u < tp;
-    const int j = pre ? u : u - tp;              // tile index inside its key set
+    const int j = pre ? u : u - tp;                 // tile index inside its key set
     const int left = (pre ? P : nkeys) - j * TILE;  // keys of the tile that exist (>= 1)
-    const __bf16* kb = (pre ? kpb : ksb) + (int64_t)j * TILE * row_stride;
-    const __bf16* vb = (pre ? vpb : vsb) + (int64_t)j * TILE * row_stride;
-    issue_row_tile<D, DQ_WAVES>(dst, kb, row_stride, left, wave, lane);
-    issue_row_tile<D, DQ_WAVES>(dst + G::ROW_TILE_BYTES, vb, row_stride, left, wave, lane);
-    issue_linear<G::IMAGE_BYTES, DQ_WAVES>(dst + 2 * G::ROW_TILE_BYTES, (pre ? ktpb : ktsb) + (int64_t)j * (D * TILE),
-                                            wave, lane);
+    if (piece < 2) {
+      const __bf16* first = (piece == 0 ? (pre ? kpb : ksb) : (pre ? vpb : vsb)) + (int64_t)j * TILE * row_stride;
+      unsigned char* d2 = dst + piece * G::ROW_TILE_BYTES;
+      if (left >= TILE)
+        issue_full_row_tile<D, DQ_WAVES>(d2, first, lane_off, wave);
+      else
+        issue_row_tile<D, DQ_WAVES>(d2, first, row_stride, left, wave, lane);
+    } else
+      issue_linear<G::IMAGE_BYTES, DQ_WAVES>(dst + 2 * G::ROW_TILE_BYTES,
+                                              (pre ? ktpb : ktsb) + (int64_t)j * (D * TILE), wave, lane);
   };
 
   f32x16 dQ[DB];
@@ -117,12 +124,19 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
 #pragma unroll
     for (int i = 0; i < 16; ++i) dQ[db][i] = 0.f;
 
-  issue(0, 0);
+  // One 32-key block = a stream of KK + DB steps of two MFMAs each, operands read from LDS PF
+  // steps ahead:  steps [0, KK): S += K Q^T, dW += V dO^T;  steps [KK, KK + DB): dQ += K^T dS,
+  // two channel blocks per step.  The two wavefronts of a SIMD overlap each other's VALU part.
+  constexpr int NB = KK + DB, PF = 2;
+
+#pragma unroll
+  for (int piece = 0; piece < 3; ++piece) issue_piece(0, 0, piece);
   for (int u = 0; u < ntiles; ++u) {
     const int buf = u & 1;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile u has landed
     __syncthreads();                      // everyone's share has; buffer buf^1 is no longer read
-    if (u + 1 < ntiles) issue(u + 1, buf ^ 1);
+    // the tile after the last one is the last one again: a harmless reload into the idle buffer
+    const int next = u + 1 < ntiles ? u + 1 : u;
     const unsigned char* kt = smem + buf * STAGE;
     const unsigned char* vt = kt + G::ROW_TILE_BYTES;
     const unsigned char* im = kt + 2 * G::ROW_TILE_BYTES;
@@ -134,40 +148,69 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 S, W;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        S[i] = 0.f;
-        W[i] = 0.f;
-      }
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 ka = lds_operand(kt + kb * 32 * G::ROWB + koff[kk]);
-        const bf16x8 va = lds_operand(vt + kb * 32 * G::ROWB + koff[kk]);
-        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, Q[kk], S, 0, 0, 0);
-        W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, dOb[kk], W, 0, 0, 0);
-      }
-      // register i: key key_tile0 + kb*32 + 8*(i/4) + 4*hf + i%4
       bf16x8 dSb[2];
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        float ds[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * a + e;
-          float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2));
-          const int key = key_tile0 + kb * 32 + 8 * a + 4 * hf + e;
-          if (!no_mask && key > limit) p = 0.f;
-          ds[e] = p * (W[i] - dl);
+      bf16x8 op0[NB], op1[NB];  // operand pair of each step (PF + 1 of them live at a time)
+      auto fetch = [&](int s) {
+        if (s < KK) {
+          op0[s] = lds_operand(kt + kb * 32 * G::ROWB + koff[s]);
+          op1[s] = lds_operand(vt + kb * 32 * G::ROWB + koff[s]);
+        } else {
+          const int v = s - KK, c2 = v / (DB / 2), db = 2 * (v % (DB / 2));
+          op0[s] = lds_operand(im + db * 32 * 128 + ioff[2 * kb + c2]);
+          op1[s] = lds_operand(im + (db + 1) * 32 * 128 + ioff[2 * kb + c2]);
         }
-        pack4(ds, 4 * a, dSb);
+      };
+#pragma unroll
+      for (int s = 0; s < PF; ++s) fetch(s);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int s = 0; s < NB; ++s) {
+        if (s + PF < NB) fetch(s + PF);
+        if (s == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Q[s], zero, 0, 0, 0);
+          W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dOb[s], zero, 0, 0, 0);
+        } else if (s < KK) {
+          S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Q[s], S, 0, 0, 0);
+          W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dOb[s], W, 0, 0, 0);
+        } else {
+          const int v = s - KK, c2 = v / (DB / 2), db = 2 * (v % (DB / 2));
+          dQ[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], dSb[c2], dQ[db], 0, 0, 0);
+          dQ[db + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dSb[c2], dQ[db + 1], 0, 0, 0);
+        }
+        // next tile's loads, one piece after each of the first odd steps of the first block
+        if (kb == 0 && (s & 1) && s < 6) issue_piece(next, buf ^ 1, s >> 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if (s == KK - 1) {
+          // register i: key key_tile0 + kb*32 + 8*(i/4) + 4*hf + i%4
+          if (no_mask) {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              float ds[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int i = 4 * a + e;
+                ds[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2)) * (W[i] - dl);
+              }
+              pack4(ds, 4 * a, dSb);
+            }
+          } else {
+#pragma unroll
+            for (int a = 0; a < 4; ++a) {
+              float ds[4];
+#pragma unroll
+              for (int e = 0; e < 4; ++e) {
+                const int i = 4 * a + e;
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2));
+                if (key_tile0 + kb * 32 + 8 * a + 4 * hf + e > limit) p = 0.f;
+                ds[e] = p * (W[i] - dl);
+              }
+              pack4(ds, 4 * a, dSb);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
       }
-#pragma unroll
-      for (int c2 = 0; c2 < 2; ++c2)
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const bf16x8 ta = lds_operand(im + db * 32 * 128 + ioff[2 * kb + c2]);
-          dQ[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ta, dSb[c2], dQ[db], 0, 0, 0);
-        }
     }
   }
 

@@ -88,6 +88,31 @@ __device__ inline void issue_row_tile(unsigned char* dst, const __bf16* first, i
   }
 }
 
+// The same for a tile whose 64 rows all exist, with the per-lane byte offsets computed once:
+// the address is a uniform tile base plus a 32-bit lane offset.
+template <int D, int NW>
+struct RowTileOffsets {
+  static constexpr int BLOCKS_PER_WAVE = Geo<D>::ROW_TILE_BYTES / 1024 / NW;
+  unsigned off[BLOCKS_PER_WAVE];
+  __device__ inline void init(int64_t row_stride, int wave, int lane) {
+    constexpr int ROWB = Geo<D>::ROWB, LANES_PER_ROW = ROWB / 16, ROWS_PER_BLOCK = 1024 / ROWB;
+#pragma unroll
+    for (int n = 0; n < BLOCKS_PER_WAVE; ++n) {
+      const int row = (wave * BLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
+      const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, ROWB)) * 8;
+      off[n] = (unsigned)((row * row_stride + col) * 2);
+    }
+  }
+};
+template <int D, int NW>
+__device__ inline void issue_full_row_tile(unsigned char* dst, const __bf16* first, const RowTileOffsets<D, NW>& o,
+                                           int wave) {
+  const char* base = reinterpret_cast<const char*>(first);
+#pragma unroll
+  for (int n = 0; n < RowTileOffsets<D, NW>::BLOCKS_PER_WAVE; ++n)
+    load16_to_lds(base + o.off[n], dst + (wave * RowTileOffsets<D, NW>::BLOCKS_PER_WAVE + n) * 1024);
+}
+
 // Linear copy of `bytes` (a multiple of 1024 * NW) global -> LDS.
 template <int BYTES, int NW>
 __device__ inline void issue_linear(unsigned char* dst, const void* src, int wave, int lane) {
