@@ -42,6 +42,15 @@ def measured_traffic(workload: str, kernel: str):
     return None
 
 
+def calibrate_copy(torch):
+    """Plain copy kernels of known size (256 MiB read, 256 MiB written each) for scaling traffic counters."""
+    src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.mul(src, 1.0, out=dst)
+    torch.cuda.synchronize()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,11 +126,7 @@ def main():
     k_prepass_ms, k_prefix_ms, k_suffix_ms, k_merge_ms = (float(v) for v in kms.mean(axis=0))
 
     if args.calibrate_copy:
-        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            torch.mul(src, 1.0, out=dst)   # one elementwise kernel: reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
+        calibrate_copy(torch)
 
     flop = wl.effective_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
@@ -236,6 +241,8 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
     torch.cuda.synchronize()
     ms_per_step = float(e0.elapsed_time(e1) / args.steps)
     kms = np.array([pa.prefix_attn_backward_timed(*bargs) for _ in range(args.steps)]).mean(axis=0)
+    if args.calibrate_copy:
+        calibrate_copy(torch)
     pairs = wl.visible_pairs(P, x.suffix_lens)
     flop = wl.backward_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12

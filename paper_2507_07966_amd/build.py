@@ -15,7 +15,10 @@ LIB = os.path.join(HERE, "libprefix_attn.so")
 SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip", "merge.hip",
            "bwd_api.cpp", "bwd_prep.hip", "bwd_dq_bf16.hip", "bwd_dkv_bf16.hip", "bwd_f32.hip"]
 # packed-fp32 code generation is switched off for every device translation unit
-DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                # MFMA results in ordinary vector registers; kernels that need more than 256 registers keep
+                # long-lived MFMA operands in the accumulation registers instead (see bwd_dkv_bf16.hip)
+                "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:

@@ -15,7 +15,10 @@
 // tile (4 x 16 KiB + statistics) goes global -> LDS with direct-to-LDS loads, double buffered,
 // one barrier per tile.  One wavefront per SIMD (the accumulators, 128 registers, and the K/V
 // columns, 64, need more than half of the register file), so the overlap of MFMA and VALU work
-// is arranged inside the wavefront: see the step stream in the kernel.
+// is arranged inside the wavefront: see the step stream in the kernel.  Built with the MFMA
+// results in ordinary vector registers (-amdgpu-mfma-vgpr-form): the compiler then keeps the
+// K/V columns in the accumulation registers, which the MFMA reads as B operands directly, and
+// the softmax VALU code needs no register-file copies.
 #include <hip/hip_runtime.h>
 
 #include "bwd.h"
@@ -144,10 +147,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   }
   for (int tile = tile0; tile < tile1; ++tile) {
     const int buf = (tile - tile0) & 1;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-      asm volatile("" : "+a"(dK[db]), "+a"(dV[db]));  // keeps the accumulators in accumulation registers: without
-                                                      // it the allocator parks some in VGPRs and copies them back
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS loads of this wavefront have landed
     __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
     // the tile after the last one is the last one again: a harmless reload into the idle buffer,

@@ -18,6 +18,14 @@ import sys
 def short_name(k: str) -> str:
     if "pass_bf16_kernel" in k:
         return "prefix_pass (bf16 MFMA)" if "Lb0E" in k else "suffix_pass (bf16 MFMA)"
+    if "bwd_dkv_kernel" in k:
+        return "bwd_dkv_prefix (bf16 MFMA)" if "Lb0E" in k else "bwd_dkv_suffix (bf16 MFMA)"
+    if "bwd_dq_kernel" in k:
+        return "bwd_dq (bf16 MFMA)"
+    if "bwd_prep" in k:
+        return "bwd_prepass"
+    if "bwd_dq_f32" in k or "bwd_dkv_f32" in k or "bwd_delta_f32" in k:
+        return "backward (fp32) " + ("dq" if "dq" in k else "dkv" if "dkv" in k else "delta")
     if "pass_f32_kernel" in k:
         return "attention pass (fp32)"
     if "merge_kernel" in k:
