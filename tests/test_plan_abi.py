@@ -143,3 +143,76 @@ def test_c5_ragged_plan_builds_fast():
     lens = (512 + rng.integers(256, 4097, size=16)).tolist()
     plan = host_plan(prefix_len=8192 * 64, suffix_lens=lens)
     coverage(plan, 28, 4, 8192 * 64, lens)
+
+
+# ---------------------------------------------------------------- backward: schedule and argument checks
+
+def key_coverage(plan, Hkv, P, lens):
+    """Every prefix key and every suffix key of every kv head lies in exactly one dK/dV work item."""
+    pre = [np.zeros(P, dtype=np.int32) for _ in range(Hkv)]
+    for g, key0, c, n in plan.key_items(0):
+        if c < 0:
+            continue
+        assert g == -1 and 0 < n <= 128 and key0 % 128 == 0 and key0 + n <= P
+        pre[c][key0:key0 + n] += 1
+    suf = [[np.zeros(S, dtype=np.int32) for S in lens] for _ in range(Hkv)]
+    for g, key0, c, n in plan.key_items(1):
+        assert 0 <= g < len(lens) and 0 <= c < Hkv and 0 < n <= 128 and key0 % 128 == 0 and key0 + n <= lens[g]
+        suf[c][g][key0:key0 + n] += 1
+    for c in range(Hkv):
+        assert (pre[c] == 1).all()
+        for g in range(len(lens)):
+            assert (suf[c][g] == 1).all()
+
+
+@pytest.mark.parametrize("Hq,Hkv,P,lens", [
+    (28, 4, 4096, [1152] * 8), (28, 4, 100, [1, 37, 300, 5]), (4, 4, 0, [70, 3]), (6, 3, 1000, [257, 256, 255]),
+])
+def test_backward_schedule_covers_every_key_once(Hq, Hkv, P, lens):
+    plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
+    key_coverage(plan, Hkv, P, lens)
+
+
+def test_backward_items_are_grouped_by_kv_head_per_xcd():
+    plan = host_plan()
+    items = plan.key_items(0)
+    for x in range(8):
+        heads = {int(it[2]) for it in items[x::8] if it[2] >= 0}
+        assert len(heads) == 1
+    k1 = plan.key_items(1)
+    work = np.asarray(plan.suffix_lens)[k1[:, 0]] - k1[:, 1]
+    assert (np.diff(work) <= 0).all()          # suffix key blocks: longest row range first
+
+
+def test_backward_workspace_and_argument_checks():
+    plan = host_plan()
+    lib = binding.load_library()
+    T, Hq, Hkv, D, P = 1152 * 8, 28, 4, 128, 4096
+    mpad = -(-T * (Hq // Hkv) // 64) * 64
+    stacked = 4 * Hkv * mpad * D * 2                       # Q, dO row-major and transposed
+    images = Hkv * (P // 64 + 8 * (1152 // 64)) * D * 64 * 2
+    need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images
+    assert need <= plan.backward_workspace_bytes <= need + 12 * 256
+    assert host_plan(dtype="f32").backward_workspace_bytes <= 2 * T * Hq * 4 + 2 * 256
+    a = 0x10000
+    big = plan.backward_workspace_bytes
+
+    def call(**kw):
+        args = dict(q=a, kp=a, vp=a, ks=a, vs=a, out=a, do=a, lse=a, dq=a, dkp=a, dvp=a, dks=a, dvs=a, ws=a, n=big)
+        args.update(kw)
+        return lib.prefix_attn_backward(plan.handle, *[args[k] for k in
+                                        ("q", "kp", "vp", "ks", "vs", "out", "do", "lse", "dq", "dkp", "dvp", "dks", "dvs", "ws", "n")], None)
+
+    assert lib.prefix_attn_backward(None, *([a] * 14), big, None) == 1
+    for name in ("q", "ks", "vs", "out", "do", "lse", "dq", "dks", "dvs", "ws", "kp", "dvp"):
+        assert call(**{name: None}) == 1, name
+    assert call(do=a + 8) == 4 and call(dkp=a + 4) == 4
+    assert call(n=big - 1) == 5
+    assert call() == 3                                      # host-only plan cannot launch
+    noprefix = host_plan(prefix_len=0)
+    st = lib.prefix_attn_backward(noprefix.handle, a, None, None, a, a, a, a, a, a, None, None, a, a, a,
+                                  noprefix.backward_workspace_bytes, None)
+    assert st == 3
+    n = ctypes.c_size_t()
+    assert lib.prefix_attn_backward_workspace(None, ctypes.byref(n)) == 1
+    assert lib.prefix_attn_plan_num_key_items(None, 0) == -1
