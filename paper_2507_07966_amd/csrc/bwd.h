@@ -26,7 +26,7 @@ struct BwdPrepArgs {
   void* qst;           // [Hkv][Mpad/64][D][64]
   void* dost;          // [Hkv][Mpad/64][D][64]
   float* lse2s;        // [Hkv][Mpad]  LSE * log2(e); rows past the end hold a huge value
-  float* deltas;       // [Hkv][Mpad]
+  float* deltas;       // [Hkv][Mpad]  -<dO, O> per stacked row (negated)
   int32_t* toks;       // [Hkv][Mpad]  packed token index of the stacked row; INT32_MAX past the end
   int64_t T;
   int64_t Mpad;        // stacked rows per kv head rounded up to ROWS_PER_ROW_TILE
@@ -44,7 +44,7 @@ struct BwdDqArgs {
   const void* kt_prefix;  // bf16: transposed K tile images [Hkv][tiles_prefix][D][64]
   const void* kt_suffix;  // bf16: [Hkv][tiles_suffix][D][64]
   const float* lse2s;     // [Hkv][Mpad] LSE * log2(e) per stacked row (from the pre-pass)
-  const float* deltas;    // [Hkv][Mpad]
+  const float* deltas;    // [Hkv][Mpad] -delta per stacked row
   void* dq;               // [T, Hq, D]
   const WorkItem* items;  // the suffix pass's list: (g, row0, c, causal extent)
   const int32_t* cu;

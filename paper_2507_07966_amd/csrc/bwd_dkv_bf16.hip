@@ -8,7 +8,8 @@
 // are the rollout's later positions (causal).  Per 32-row block:
 //   S  = Q K^T                   (A = Q rows from LDS,  B = K in registers)
 //   dW = dO V^T                  (A = dO rows from LDS, B = V in registers)
-//   W  = exp2(c S - LSE log2 e),  dS = W * (dW - delta)   (VALU; LSE/delta per row from LDS)
+//   W  = exp2(c S - LSE log2 e),  dS = W * (dW - delta)   (VALU; the dW accumulator starts from
+//                                                          -delta, read from LDS in register order)
 //   dV^T += dO^T W               (A = transposed dO image, B = W packed to bf16)
 //   dK^T += Q^T dS               (A = transposed Q image,  B = dS packed to bf16)
 // The stacked, row-major Q/dO copies and their transposed images come from the pre-pass; a
@@ -53,7 +54,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   const int l32 = lane & 31, hf = lane >> 5;
   const int off_g = CAUSAL ? cu[it.g] : 0;
   const int end_g = CAUSAL ? cu[it.g + 1] : 0;
-  const int64_t row_stride = (int64_t)Hkv * D;
 
   // ---- this lane's key column: K and V in registers (zeros past the end of the block)
   const int kloc = wave * 32 + l32;        // key inside the block
@@ -100,25 +100,26 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   // The loads of a tile are issued in four pieces so they can be spread over the MFMA stream.
   RowTileOffsets<D, KEY_WAVES> lane_off;
   lane_off.init(D, wave, lane);
+  const rsrc_t r_qs = make_rsrc(qs_c), r_dos = make_rsrc(dos_c), r_qst = make_rsrc(qst_c), r_dost = make_rsrc(dost_c);
+  const rsrc_t r_lse = make_rsrc(lse_c), r_del = make_rsrc(del_c), r_tok = make_rsrc(tok_c);
   auto issue_piece = [&](int tile, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
-    const int64_t e0 = (int64_t)tile * TILE * D;  // first element of the tile in each of the four arrays
+    const unsigned b0 = (unsigned)tile * (TILE * D * 2);  // byte offset of the tile in each of the four arrays
     if (piece == 0) {
       if (wave == 0) {  // per-row statistics: 64 dwords each, lane l's word lands at word l
         unsigned char* st = dst + 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES;
-        const int64_t m = (int64_t)tile * TILE + lane;
-        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(lse_c + m), (PA_LDS_PTR(void))st, 4, 0, 0);
-        __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(del_c + m), (PA_LDS_PTR(void))(st + TILE * 4), 4, 0, 0);
-        if (CAUSAL)
-          __builtin_amdgcn_global_load_lds((PA_GLB_PTR(const void))(tok_c + m), (PA_LDS_PTR(void))(st + 2 * TILE * 4), 4, 0, 0);
+        const unsigned m4 = (unsigned)tile * (TILE * 4);
+        load_dword_to_lds(r_lse, st, lane * 4, m4);
+        load_dword_to_lds(r_del, st + TILE * 4, lane * 4, m4);
+        if (CAUSAL) load_dword_to_lds(r_tok, st + 2 * TILE * 4, lane * 4, m4);
       }
-      issue_full_row_tile<D, KEY_WAVES>(dst, qs_c + e0, lane_off, wave);
+      issue_full_row_tile<D, KEY_WAVES>(dst, r_qs, b0, lane_off, wave);
     } else if (piece == 1) {
-      issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, dos_c + e0, lane_off, wave);
+      issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, r_dos, b0, lane_off, wave);
     } else if (piece == 2) {
-      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, qst_c + e0, wave, lane);
+      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, r_qst, b0, wave, lane);
     } else {
-      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, dost_c + e0, wave, lane);
+      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, r_dost, b0, wave, lane);
     }
   };
 
@@ -138,8 +139,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   // four slices per block and interleaved with the MFMAs of later steps, so both pipes stay busy
   // although only one wavefront runs per SIMD.
   constexpr int NSW = 2 * KK, NDK = 4 * DB, NS = NSW + NDK, PF = 2;
-  static_assert(KK % 4 == 0 || KK == 4, "slice schedule assumes KK in {4, 8}");
-  constexpr int SLICE_STRIDE = KK / 4;
 
   if (tile0 < tile1) {
 #pragma unroll
@@ -160,13 +159,16 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
 
     f32x16 S[2], W[2];
     bf16x8 Pb[2][2], dSb[2][2];
-    f32x4 l4[2][4], d4[2][4];  // per-slice statistics, each loaded one slice slot before its use
+    f32x4 l4[2][4];           // LSE * log2(e) of a slice's four rows, loaded one slot before its use
     i32x4 p4[2][4];
     bf16x8 op0[NS], op1[NS];  // operand pair of each step (only PF+1 of them are live at a time)
 
+    // steps [0, NSW): block rb = s % 2, contraction step kk = s / 2, i.e. four independent
+    // accumulation chains (S and dW of both blocks): one wavefront alone cannot issue dependent
+    // MFMAs back to back at full rate
     auto fetch = [&](int s) {
       if (s < NSW) {
-        const int rb = s / KK, kk = s % KK;
+        const int rb = s % 2, kk = s / 2;
         op0[s] = lds_operand(qt + rb * 32 * G::ROWB + roff[kk]);
         op1[s] = lds_operand(dt + rb * 32 * G::ROWB + roff[kk]);
       } else {
@@ -178,10 +180,10 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     auto load_stats = [&](int rb, int a) {
       const int r0 = rb * 32 + 8 * a + 4 * hf;
       l4[rb][a] = *reinterpret_cast<const f32x4*>(st + r0);
-      d4[rb][a] = *reinterpret_cast<const f32x4*>(st + TILE + r0);
       if (CAUSAL) p4[rb][a] = *reinterpret_cast<const i32x4*>(st + 2 * TILE + r0);
     };
-    // slice a of block rb: registers [4a, 4a+4) = rows rb*32 + 8a + 4hf + (0..3) of the tile, this lane's key
+    // slice a of block rb: registers [4a, 4a+4) = rows rb*32 + 8a + 4hf + (0..3) of the tile, this
+    // lane's key.  W already holds dW - delta (its accumulator started from -delta).
     auto slice = [&](int rb, int a) {
       float p[4], ds[4];
 #pragma unroll
@@ -189,12 +191,22 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         const int i = 4 * a + e;
         p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[rb][i], c_log2, -l4[rb][a][e]));
         if (CAUSAL && (unsigned)p4[rb][a][e] - tkey >= tspan) p[e] = 0.f;
-        ds[e] = p[e] * (W[rb][i] - d4[rb][a][e]);
+        ds[e] = p[e] * W[rb][i];
       }
       pack4(p, 4 * a, Pb[rb]);
       pack4(ds, 4 * a, dSb[rb]);
     };
 
+    // dW accumulators start from -delta of their rows: register i is row rb*32 + 8*(i/4) + 4*hf + i%4,
+    // so four 16-byte reads of the (negated) delta array fill a block's 16 registers
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        const f32x4 nd = *reinterpret_cast<const f32x4*>(st + TILE + rb * 32 + 8 * a + 4 * hf);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) W[rb][4 * a + e] = nd[e];
+      }
 #pragma unroll
     for (int s = 0; s < PF; ++s) fetch(s);
     __builtin_amdgcn_sched_barrier(0);
@@ -202,15 +214,14 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     for (int s = 0; s < NS; ++s) {
       if (s + PF < NS) fetch(s + PF);
       if (s < NSW) {
-        const int rb = s / KK, kk = s % KK;
+        const int rb = s % 2, kk = s / 2;
         if (kk == 0) {
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Kb[kk], zero, 0, 0, 0);
-          W[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], Vb[kk], zero, 0, 0, 0);
         } else {
           S[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Kb[kk], S[rb], 0, 0, 0);
-          W[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], Vb[kk], W[rb], 0, 0, 0);
         }
+        W[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], Vb[kk], W[rb], 0, 0, 0);
       } else {
         const int u = s - NSW, blk = u / (2 * DB), c2 = (u / DB) % 2, db = u % DB;
         dV[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Pb[blk][c2], dV[db], 0, 0, 0);
@@ -218,16 +229,23 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
       }
       // next tile's loads, one piece after each of the first odd steps
       if ((s & 1) && s < 8) issue_piece(next_tile, buf ^ 1, s >> 1);
-      __builtin_amdgcn_sched_barrier(0);  // MFMAs first, the VALU slice then runs in their shadow
-      // softmax slices: block 0 after S[0], dW[0] are complete, block 1 after S[1], dW[1]; the
-      // statistics of a slice are read one slot earlier
+      __builtin_amdgcn_sched_barrier(0);
+      // softmax slices: block 0 once both blocks' S and dW are complete, block 1 during the first
+      // dV/dK steps of block 0; a slice's LSE values are read one slot earlier
+      if (s == NSW - 2) load_stats(0, 0);
+      if (s == NSW - 1) {
 #pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        if (s == KK + (a - 1) * SLICE_STRIDE) load_stats(0, a);
-        if (s == 2 * KK + (a - 1) * SLICE_STRIDE) load_stats(1, a);
-        if (s == KK + a * SLICE_STRIDE) slice(0, a);
-        if (s == 2 * KK + a * SLICE_STRIDE) slice(1, a);
+        for (int a = 0; a < 4; ++a) {
+          if (a + 1 < 4) load_stats(0, a + 1); else load_stats(1, 0);
+          slice(0, a);
+        }
       }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+        if (s == NSW + a) {
+          if (a + 1 < 4) load_stats(1, a + 1);
+          slice(1, a);
+        }
       __builtin_amdgcn_sched_barrier(0);
     }
   }

@@ -68,7 +68,7 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
       }
       const int64_t srow = (int64_t)it.c * Mpad + (int64_t)off_g * group + m;  // stacked row over all packed tokens
       lse2 = lse2s[srow];
-      dl = deltas[srow];
+      dl = -deltas[srow];  // the array holds -delta
     } else {
       pos = -1;  // sees nothing: every weight is masked to zero
       orow = -1;

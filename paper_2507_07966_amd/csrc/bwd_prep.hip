@@ -7,7 +7,7 @@
 //   - their transposed tile images [D][64] in the LDS-ready layout of the MFMA A operand
 //     (columns inside every group of 16 in the order 0-3, 8-11, 4-7, 12-15; 16-byte chunk j of
 //     row d stored at chunk position j ^ ((d >> 1) & 7)),
-//   - per row: LSE * log2(e), delta and the packed token index.
+//   - per row: LSE * log2(e), -delta and the packed token index.
 // Rows past the last stacked row are zero, with a huge LSE (their weights become exactly 0)
 // and token index INT32_MAX.  Cost: Q, dO and O are read once and Q, dO written twice.
 #include <hip/hip_runtime.h>
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(
 #pragma unroll
     for (int s = CPR / 2; s >= 1; s >>= 1) part += __shfl_xor(part, s, CPR);
     if (ch == 0) {
-      deltas[srow] = part;
+      deltas[srow] = -part;  // negated: the dK/dV pass starts its dW accumulators from it
       lse2s[srow] = valid ? lse[(int64_t)h * T + t] * LOG2E : LSE_PAST_END;
       toks[srow] = t;
     }

@@ -123,6 +123,58 @@ __device__ inline void issue_linear(unsigned char* dst, const void* src, int wav
   for (int n = 0; n < BLOCKS_PER_WAVE; ++n) load16_to_lds(s + n * 1024, dst + (wave * BLOCKS_PER_WAVE + n) * 1024);
 }
 
+// ---- the same copies through buffer instructions: a 128-bit resource descriptor in scalar
+// registers (base address, no stride, 2 GiB range, raw dword format), a uniform byte offset in
+// a scalar register, a 32-bit lane offset and an immediate.  No vector address arithmetic at
+// all, and offsets past the range read as zero instead of faulting (a range shorter than the
+// tile replaces explicit clamping of a ragged last tile).
+#if defined(__HIP_DEVICE_COMPILE__)
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+__device__ inline rsrc_t make_rsrc(const void* base, int64_t bytes = 0x7fffffff) {
+  const int n = bytes < 0 ? 0 : (bytes > 0x7fffffff ? 0x7fffffff : (int)bytes);
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, n, 0x00020000);
+}
+template <int D, int NW>
+__device__ inline void issue_full_row_tile(unsigned char* dst, rsrc_t r, unsigned tile_byte_offset,
+                                           const RowTileOffsets<D, NW>& o, int wave) {
+#pragma unroll
+  for (int n = 0; n < RowTileOffsets<D, NW>::BLOCKS_PER_WAVE; ++n)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(
+        r, (PA_LDS_PTR(void))(dst + (wave * RowTileOffsets<D, NW>::BLOCKS_PER_WAVE + n) * 1024), 16, o.off[n],
+        tile_byte_offset, 0, 0);
+}
+template <int BYTES, int NW>
+__device__ inline void issue_linear(unsigned char* dst, rsrc_t r, unsigned byte_offset, int wave, int lane) {
+  constexpr int BLOCKS_PER_WAVE = BYTES / 1024 / NW;
+  static_assert(BLOCKS_PER_WAVE >= 1 && BLOCKS_PER_WAVE <= 4 && BYTES % (1024 * NW) == 0, "whole blocks, small immediates");
+  const unsigned soff = byte_offset + (unsigned)(wave * BLOCKS_PER_WAVE) * 1024u;
+  unsigned char* d0 = dst + (wave * BLOCKS_PER_WAVE) * 1024;
+  const unsigned voff = (unsigned)lane * 16u;
+  // The instruction's immediate offset is added to the memory address AND to the LDS address, so
+  // all blocks name the same LDS base.  It must be a literal, hence no loop.
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))d0, 16, voff, soff, 0, 0);
+  if constexpr (BLOCKS_PER_WAVE > 1)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))d0, 16, voff, soff, 1024, 0);
+  if constexpr (BLOCKS_PER_WAVE > 2)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))d0, 16, voff, soff, 2048, 0);
+  if constexpr (BLOCKS_PER_WAVE > 3)
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))d0, 16, voff, soff, 3072, 0);
+}
+// one dword per lane: lane l's word lands at dst + 4*l
+__device__ inline void load_dword_to_lds(rsrc_t r, unsigned char* dst, unsigned lane_byte_offset, unsigned byte_offset) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))dst, 4, lane_byte_offset, byte_offset, 0, 0);
+}
+#else
+// The host pass of hipcc still parses kernel bodies but has no buffer-resource type: empty stand-ins.
+struct rsrc_t {};
+__device__ inline rsrc_t make_rsrc(const void*, int64_t = 0) { return {}; }
+template <int D, int NW>
+__device__ inline void issue_full_row_tile(unsigned char*, rsrc_t, unsigned, const RowTileOffsets<D, NW>&, int) {}
+template <int BYTES, int NW>
+__device__ inline void issue_linear(unsigned char*, rsrc_t, unsigned, int, int) {}
+__device__ inline void load_dword_to_lds(rsrc_t, unsigned char*, unsigned, unsigned) {}
+#endif
+
 // Pack four fp32 accumulator registers [r0, r0+4) of a 16-register block into the B operand
 // pair Pb[2]: register r goes to operand r >> 3, slot r & 7.
 __device__ inline void pack4(const float (&x)[4], int r0, bf16x8 (&Pb)[2]) {
