@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--workload", default="C3")
     ap.add_argument("--direction", choices=("forward", "backward"), default="forward",
                     help="forward (default): the prefill attention hot path; backward: its gradient pass")
+    ap.add_argument("--prefix-shards", type=int, default=0,
+                    help="n > 0: time what ONE device of an n-way prefix-key-sharded group computes (its shard's "
+                         "partial pass + the n-way merge); the exchange of partials between devices is not part of it")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -103,6 +106,8 @@ def main():
         pa.prefix_attn_forward(*fwd_args)
         pa.prefix_attn_lse(plan, ws, lse)
 
+    if args.prefix_shards > 0:
+        return sharded_main(args, pa, wl, torch, w, x, dev, out, lse)
     if args.direction == "backward":
         step()
         return backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse)
@@ -207,6 +212,85 @@ def main():
         result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - o_ref).max()),
                                       "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
                                       "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
+    print(json.dumps(result), flush=True)
+
+
+def sharded_main(args, pa, wl, torch, w, x, dev, out, lse):
+    """One device's share when the P prefix keys are split into n shards (paper Sec. 5.2, sequence parallelism):
+    a partial pass over P/n prefix keys (+ the rollouts' own keys on this device) for ALL suffix rows, then the
+    n-way merge of the partials it would have received.  The other n-1 partials are produced here by the same
+    device beforehand (untimed) so the merge reads real data."""
+    n = args.prefix_shards
+    T, P = x.total_suffix, w.prefix_len
+    assert P % n == 0 and P > 0, "prefix_len must be divisible by the number of shards"
+    Ps = P // n
+    plan = pa.prefix_attn_plan(w.num_q_heads, w.num_kv_heads, w.head_dim, Ps, x.suffix_lens, w.scale, dtype=w.dtype, device=0)
+    ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+    po = [torch.empty((T, w.num_q_heads, w.head_dim), dtype=torch.float32, device="cuda") for _ in range(n)]
+    pl = [torch.empty((T, w.num_q_heads), dtype=torch.float32, device="cuda") for _ in range(n)]
+
+    def partial(i):
+        a, b = i * Ps, (i + 1) * Ps
+        pa.prefix_attn_forward_partial(plan, dev["q"], dev["k_prefix"][a:b], dev["v_prefix"][a:b],
+                                       dev["k_suffix"] if i == 0 else None, dev["v_suffix"] if i == 0 else None,
+                                       i == 0, po[i], pl[i], ws)
+
+    for i in range(1, n):
+        partial(i)
+
+    def step():
+        partial(0)
+        pa.prefix_attn_merge_partials(plan, po, pl, out, lse)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    t_part = t_merge = 0.0
+    for _ in range(args.steps):
+        ev[0].record()
+        partial(0)
+        ev[1].record()
+        pa.prefix_attn_merge_partials(plan, po, pl, out, lse)
+        ev[2].record()
+        torch.cuda.synchronize()
+        t_part += ev[0].elapsed_time(ev[1])
+        t_merge += ev[1].elapsed_time(ev[2])
+    t_part /= args.steps
+    t_merge /= args.steps
+    ms = t_part + t_merge
+    flop_dev = 4 * w.head_dim * w.num_q_heads * (T * Ps + wl.visible_pairs(0, x.suffix_lens))
+    e = 2 if w.dtype == "bf16" else 4
+    merge_bytes = T * w.num_q_heads * (n * (w.head_dim + 1) * 4 + w.head_dim * e + 4)
+    result = {
+        "metric": "effective attention TFLOP/s of one device in a prefix-sharded group (exchange excluded)",
+        "value": round(flop_dev / (ms * 1e-3) * 1e-12, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True, "scaling": "strong",
+        "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name} with the prefix keys in {n} shards: {w.note}", "prefix_shards": n,
+                   "prefix_keys_per_shard": Ps, "total_suffix_tokens": T},
+        "kernel_ms": {"shard_partial_pass_incl_suffix": round(t_part, 4), "merge_of_partials": round(t_merge, 4)},
+        "roofline": {"kernel": "merge_partials", "bound": "hbm", "achieved": round(merge_bytes / (t_merge * 1e-3) * 1e-9, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(merge_bytes / (t_merge * 1e-3) * 1e-9 / HBM_PEAK_GBS, 4),
+                     "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import cref
+        rows = np.sort(wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 2, seed=1))[:64]
+        t0 = time.perf_counter()
+        ro, rl, thr = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens,
+                                                   w.scale, rows=rows)
+        t_cpu = time.perf_counter() - t0
+        off = np.concatenate([[0], np.cumsum(x.suffix_lens.astype(np.int64))])
+        gi = np.searchsorted(off, rows, side="right") - 1
+        cpu_flop = 4 * w.head_dim * w.num_q_heads * int(np.sum(P + (rows - off[gi]) + 1))
+        o_gpu = out[torch.from_numpy(rows).cuda()].float().cpu().numpy().astype(np.float64)
+        l_gpu = lse[:, torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
+        result["cpu_baseline"] = {"value": round(cpu_flop / t_cpu * 1e-12, 6), "unit": "TFLOP/s", "cores": int(thr),
+                                  "kind": "oracle", "sample": f"{len(rows)} seeded query rows x {w.num_q_heads} heads "
+                                  f"against the whole (unsharded) key set (fp64, {t_cpu:.1f} s)"}
+        result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - ro).max()),
+                                      "lse_max_abs": float(np.abs(l_gpu - rl).max())}
     print(json.dumps(result), flush=True)
 
 

@@ -112,6 +112,35 @@ int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, con
 int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out,
                     void* hip_stream);
 
+/* ---- composition over key shards (paper Sec. 5.2: the prefill is spread over devices by
+ *      sequence parallelism; here the shared prefix keys of one question are split into shards,
+ *      each device attends all suffix rows to its shard, and the partial results are combined).
+ *      These two calls are the part one device computes; moving partials between devices is the
+ *      caller's business. ---- */
+
+/* Like prefix_attn_forward, but the result stays an fp32 partial result over the keys this call
+ * covers:  o_partial [T, Hq, D] (normalised over those keys), lse_partial [T, Hq] (natural log).
+ * The plan's prefix_len is the number of prefix keys of THIS shard (k_prefix / v_prefix hold only
+ * them).  include_suffix != 0: the keys covered are the shard and every rollout's own suffix keys
+ * (exactly one shard of a sharded call does this); include_suffix == 0: the shard's prefix keys
+ * only (needs prefix_len > 0, else PA_ERR_SHAPE; k_suffix / v_suffix may then be NULL).
+ * Partials over disjoint key sets are combined with prefix_attn_merge_partials. */
+int prefix_attn_forward_partial(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                                const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                                int32_t include_suffix, float* o_partial, float* lse_partial,
+                                void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Combine n partial results over disjoint key sets of the same queries:
+ *   LSE = ln sum_i e^{LSE_i},   out = sum_i e^{LSE_i - LSE} O_i,
+ * which is the softmax over the union of the key sets.  o_partials / lse_partials are HOST arrays
+ * of n DEVICE pointers ([T, Hq, D] and [T, Hq] fp32, 1 <= n <= PA_MAX_PARTIALS, else
+ * PA_ERR_SHAPE).  out [T, Hq, D] has the plan's dtype; lse_out [Hq, T] fp32 may be NULL.  Only
+ * T, Hq, D and the dtype of `plan` are used. */
+#define PA_MAX_PARTIALS 16
+int prefix_attn_merge_partials(const prefix_attn_plan_t* plan, int32_t n, const float* const* o_partials,
+                               const float* const* lse_partials, void* out, float* lse_out,
+                               void* hip_stream);
+
 /* ---- backward (the policy model is trained through this attention: paper Eq. 1, Sec. 5.2) ----
  *
  * Given d_out = dL/d(out), computes the gradients of L with respect to the five inputs of the

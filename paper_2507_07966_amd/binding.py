@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forw
                     "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
                     "prefix_attn_plan_items", "prefix_attn_plan_total_tokens", "prefix_attn_backward_workspace",
                     "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_plan_num_key_items",
-                    "prefix_attn_plan_key_items")
+                    "prefix_attn_plan_key_items", "prefix_attn_forward_partial", "prefix_attn_merge_partials")
 
 
 class PrefixAttnError(RuntimeError):
@@ -75,6 +75,10 @@ def load_library():
     lib.prefix_attn_plan_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     lib.prefix_attn_plan_total_tokens.restype = ctypes.c_int64
     lib.prefix_attn_plan_total_tokens.argtypes = [vp]
+    lib.prefix_attn_forward_partial.restype = ctypes.c_int
+    lib.prefix_attn_forward_partial.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
+    lib.prefix_attn_merge_partials.restype = ctypes.c_int
+    lib.prefix_attn_merge_partials.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
     lib.prefix_attn_backward_workspace.restype = ctypes.c_int
     lib.prefix_attn_backward_workspace.argtypes = [vp, ctypes.POINTER(sz)]
     lib.prefix_attn_backward.restype = ctypes.c_int
@@ -225,6 +229,28 @@ def prefix_attn_forward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suf
     if st:
         raise PrefixAttnError(st, "prefix_attn_forward_timed")
     return float(ms[0]), float(ms[1]), float(ms[2]), float(ms[3])
+
+
+def prefix_attn_forward_partial(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, include_suffix: bool,
+                                o_partial, lse_partial, workspace, stream=None) -> None:
+    """prefix_attn_forward_partial of the C ABI: fp32 partial (o [T,Hq,D], lse [T,Hq]) over this plan's prefix
+    shard, plus the rollouts' own keys when include_suffix."""
+    st = load_library().prefix_attn_forward_partial(
+        plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix), _ptr(v_suffix), int(bool(include_suffix)),
+        _ptr(o_partial), _ptr(lse_partial), _ptr(workspace), _nbytes(workspace, plan.workspace_bytes), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_forward_partial")
+
+
+def prefix_attn_merge_partials(plan: PrefixAttnPlan, o_partials, lse_partials, out, lse_out=None, stream=None) -> None:
+    """prefix_attn_merge_partials of the C ABI: combine fp32 partials over disjoint key sets into out (and lse_out [Hq,T])."""
+    n = len(o_partials)
+    arr = ctypes.c_void_p * max(n, 1)
+    st = load_library().prefix_attn_merge_partials(
+        plan.handle, n, arr(*[_ptr(t) for t in o_partials]), arr(*[_ptr(t) for t in lse_partials]), _ptr(out),
+        _ptr(lse_out), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_merge_partials")
 
 
 def prefix_attn_lse(plan: PrefixAttnPlan, workspace, lse_out, stream=None) -> None:

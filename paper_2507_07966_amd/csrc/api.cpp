@@ -9,17 +9,29 @@ namespace {
 
 bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// What a forward call leaves behind.
+enum Mode {
+  FULL = 0,            // out in the plan's dtype, merged LSE in the workspace
+  PARTIAL_ALL = 1,     // fp32 partial over prefix shard + suffix keys, in caller buffers
+  PARTIAL_PREFIX = 2,  // fp32 partial over the prefix shard only, in caller buffers
+};
+
 // Checks, then the launches (layout pre-pass, prefix pass, suffix pass, merge).  When `ev` is
-// non-null it holds 5 events recorded before, between and after them.
+// non-null it holds 5 events recorded before, between and after them.  In the partial modes
+// `out` is the fp32 partial output and `lse_partial` its [T, Hq] LSE.
 int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix, const void* v_prefix,
                     const void* k_suffix, const void* v_suffix, void* out, void* workspace, size_t workspace_bytes,
-                    void* hip_stream, hipEvent_t* ev) {
-  if (!plan || !q || !k_suffix || !v_suffix || !out || !workspace) return PA_ERR_NULL;
+                    void* hip_stream, hipEvent_t* ev, Mode mode = FULL, float* lse_partial = nullptr) {
+  if (!plan || !q || !out || !workspace) return PA_ERR_NULL;
+  const bool with_suffix = mode != PARTIAL_PREFIX;
+  if (with_suffix && (!k_suffix || !v_suffix)) return PA_ERR_NULL;
+  if (mode != FULL && !lse_partial) return PA_ERR_NULL;
   const prefix_attn_desc_t& d = plan->desc;
   const bool has_prefix = d.prefix_len > 0;
+  if (!with_suffix && !has_prefix) return PA_ERR_SHAPE;  // a prefix-only partial over no keys
   if (has_prefix && (!k_prefix || !v_prefix)) return PA_ERR_NULL;
-  if (misaligned(q) || misaligned(k_suffix) || misaligned(v_suffix) || misaligned(out) || misaligned(workspace))
-    return PA_ERR_ALIGN;
+  if (misaligned(q) || misaligned(out) || misaligned(workspace) || misaligned(lse_partial)) return PA_ERR_ALIGN;
+  if (with_suffix && (misaligned(k_suffix) || misaligned(v_suffix))) return PA_ERR_ALIGN;
   if (has_prefix && (misaligned(k_prefix) || misaligned(v_prefix))) return PA_ERR_ALIGN;
   if (workspace_bytes < plan->ws_bytes) return PA_ERR_WORKSPACE;
   if (d.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan
@@ -55,7 +67,7 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     t.vt_off = plan->d_vt_off;
     t.P = d.prefix_len;
     t.tiles_prefix = plan->tiles_prefix;
-    t.tiles_suffix = plan->tiles_suffix;
+    t.tiles_suffix = with_suffix ? plan->tiles_suffix : 0;
     t.G = d.num_rollouts;
     t.Hkv = d.num_kv_heads;
     t.D = d.head_dim;
@@ -68,14 +80,15 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     a.vt = ws + plan->off_vtp;
     a.vt_off = nullptr;
     a.vt_tiles_per_head = plan->tiles_prefix;
-    a.o_part = o1;
-    a.lse_part = lse1;
+    a.o_part = with_suffix ? o1 : static_cast<float*>(out);  // a prefix-only partial goes straight to the caller
+    a.lse_part = with_suffix ? lse1 : lse_partial;
     a.items = plan->d_items[0];
     a.num_items = (int64_t)plan->items[0].size();
     a.causal = false;
     if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[2], hs) != hipSuccess) return PA_ERR_HIP;
+  if (!with_suffix) return PA_OK;
   a.k = k_suffix;
   a.v = v_suffix;
   a.vt = ws + plan->off_vts;
@@ -95,10 +108,10 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   m.o2 = o2;
   m.lse2 = lse2;
   m.out = out;
-  m.lse = lse;
+  m.lse = mode == FULL ? lse : lse_partial;
   m.rows = plan->T * d.num_q_heads;
   m.D = d.head_dim;
-  m.dtype = d.dtype;
+  m.dtype = mode == FULL ? d.dtype : (int32_t)PA_F32;
   m.has_prefix = has_prefix;
   if (pa::launch_merge(m, hip_stream) != 0) return PA_ERR_HIP;
   if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
@@ -132,6 +145,40 @@ int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, con
   for (int i = 0; i < 5; ++i)
     if (ev[i]) (void)hipEventDestroy(ev[i]);
   return st;
+}
+
+int prefix_attn_forward_partial(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                                const void* v_prefix, const void* k_suffix, const void* v_suffix,
+                                int32_t include_suffix, float* o_partial, float* lse_partial, void* workspace,
+                                size_t workspace_bytes, void* hip_stream) {
+  return enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, o_partial, workspace, workspace_bytes,
+                         hip_stream, nullptr, include_suffix ? PARTIAL_ALL : PARTIAL_PREFIX, lse_partial);
+}
+
+int prefix_attn_merge_partials(const prefix_attn_plan_t* plan, int32_t n, const float* const* o_partials,
+                               const float* const* lse_partials, void* out, float* lse_out, void* hip_stream) {
+  if (!plan || !o_partials || !lse_partials || !out) return PA_ERR_NULL;
+  if (n < 1 || n > PA_MAX_PARTIALS) return PA_ERR_SHAPE;
+  pa::MergeNArgs a{};
+  for (int i = 0; i < n; ++i) {
+    if (!o_partials[i] || !lse_partials[i]) return PA_ERR_NULL;
+    if (misaligned(o_partials[i]) || misaligned(lse_partials[i])) return PA_ERR_ALIGN;
+    a.o[i] = o_partials[i];
+    a.lse[i] = lse_partials[i];
+  }
+  if (misaligned(out) || misaligned(lse_out)) return PA_ERR_ALIGN;
+  if (plan->desc.device < 0) return PA_ERR_UNSUPPORTED;
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess || cur != plan->desc.device) return PA_ERR_HIP;
+  a.out = out;
+  a.lse_out = lse_out;
+  a.T = plan->T;
+  a.n = n;
+  a.Hq = plan->desc.num_q_heads;
+  a.D = plan->desc.head_dim;
+  a.dtype = plan->desc.dtype;
+  if (pa::launch_merge_n(a, hip_stream) != 0) return PA_ERR_HIP;
+  return PA_OK;
 }
 
 int prefix_attn_lse(const prefix_attn_plan_t* plan, const void* workspace, float* lse_out, void* hip_stream) {

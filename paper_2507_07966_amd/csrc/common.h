@@ -89,6 +89,16 @@ struct VtArgs {
 };
 int launch_vt_images(const VtArgs& a, void* stream);
 int launch_merge(const MergeArgs& a, void* stream);
+// n-way merge of fp32 partials (see prefix_attn_merge_partials).
+struct MergeNArgs {
+  const float* o[PA_MAX_PARTIALS];
+  const float* lse[PA_MAX_PARTIALS];
+  void* out;        // [T, Hq, D] in `dtype`
+  float* lse_out;   // [Hq, T] or null
+  int64_t T;
+  int32_t n, Hq, D, dtype;
+};
+int launch_merge_n(const MergeNArgs& a, void* stream);
 int launch_lse_export(const float* lse_th, float* lse_ht, int64_t T, int32_t Hq, void* stream);
 
 }  // namespace pa

@@ -51,6 +51,38 @@ __global__ __launch_bounds__(256) void merge_kernel(const float* __restrict__ o1
   }
 }
 
+// n-way merge: one thread handles 4 consecutive channels of one (token, head) row.
+template <bool OUT_BF16>
+__global__ __launch_bounds__(256) void merge_n_kernel(MergeNArgs a) {
+  const int per_row = a.D / 4;
+  const int64_t rows = a.T * a.Hq;
+  const int64_t total = rows * per_row;
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += stride) {
+    const int64_t row = idx / per_row;
+    const int ch = (int)(idx - row * per_row);
+    float m = -INFINITY;
+    for (int i = 0; i < a.n; ++i) m = fmaxf(m, a.lse[i][row]);
+    float tot = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < a.n; ++i) {
+      const float w = expf(a.lse[i][row] - m);  // a partial over no keys has LSE = -inf and weight 0
+      tot += w;
+      acc += w * *reinterpret_cast<const f32x4*>(a.o[i] + idx * 4);
+    }
+    const f32x4 r = acc * (1.0f / tot);
+    if (OUT_BF16) {
+      *reinterpret_cast<bf16x4*>(static_cast<__bf16*>(a.out) + idx * 4) = __builtin_convertvector(r, bf16x4);
+    } else {
+      *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + idx * 4) = r;
+    }
+    if (ch == 0 && a.lse_out) {
+      const int64_t t = row / a.Hq, h = row - t * a.Hq;
+      a.lse_out[h * a.T + t] = m + logf(tot);
+    }
+  }
+}
+
 // [T, Hq] -> [Hq, T]
 __global__ __launch_bounds__(256) void lse_export_kernel(const float* __restrict__ in, float* __restrict__ out,
                                                          int64_t T, int Hq) {
@@ -74,6 +106,19 @@ int launch_merge(const MergeArgs& a, void* stream) {
     merge_kernel<true><<<blocks, 256, 0, s>>>(a.o1, a.lse1, a.o2, a.lse2, a.out, a.lse, a.rows, a.D, a.has_prefix);
   else
     merge_kernel<false><<<blocks, 256, 0, s>>>(a.o1, a.lse1, a.o2, a.lse2, a.out, a.lse, a.rows, a.D, a.has_prefix);
+  return (int)hipGetLastError();
+}
+
+int launch_merge_n(const MergeNArgs& a, void* stream) {
+  const int64_t total = a.T * a.Hq * (a.D / 4);
+  if (total == 0) return 0;
+  const int64_t want = (total + 255) / 256;
+  const int blocks = (int)(want < 256 * 32 ? want : 256 * 32);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (a.dtype == PA_BF16)
+    merge_n_kernel<true><<<blocks, 256, 0, s>>>(a);
+  else
+    merge_n_kernel<false><<<blocks, 256, 0, s>>>(a);
   return (int)hipGetLastError();
 }
 

@@ -216,3 +216,27 @@ def test_backward_workspace_and_argument_checks():
     n = ctypes.c_size_t()
     assert lib.prefix_attn_backward_workspace(None, ctypes.byref(n)) == 1
     assert lib.prefix_attn_plan_num_key_items(None, 0) == -1
+
+
+def test_sharded_calls_check_arguments():
+    plan = host_plan()
+    lib = binding.load_library()
+    a = 0x10000
+    big = plan.workspace_bytes
+    fp = lambda *p: lib.prefix_attn_forward_partial(plan.handle, *p)
+    assert fp(a, a, a, a, a, 1, a, None, a, big, None) == 1          # the partial's LSE is required
+    assert fp(a, a, a, None, a, 1, a, a, a, big, None) == 1          # suffix keys needed when included
+    assert fp(a, a, a, None, None, 0, a, a, a, big, None) == 3       # prefix-only: suffix may be NULL; host-only plan
+    assert fp(a, a, a, a, a, 1, a, a + 4, a, big, None) == 4
+    noprefix = host_plan(prefix_len=0)
+    assert lib.prefix_attn_forward_partial(noprefix.handle, a, None, None, None, None, 0, a, a, a,
+                                           noprefix.workspace_bytes, None) == 2   # a partial over no keys
+    ptrs = (ctypes.c_void_p * 17)(*([a] * 17))
+    mp = lambda n, o=ptrs, l=ptrs, out=a, lse=a: lib.prefix_attn_merge_partials(plan.handle, n, o, l, out, lse, None)
+    assert mp(0) == 2 and mp(17) == 2
+    assert mp(2, None) == 1 and mp(2, out=None) == 1
+    holes = (ctypes.c_void_p * 2)(a, None)
+    assert mp(2, holes) == 1
+    odd = (ctypes.c_void_p * 2)(a, a + 8)
+    assert mp(2, ptrs, odd) == 4
+    assert mp(3) == 3 and mp(3, lse=None) == 3                        # host-only plan cannot launch
