@@ -162,6 +162,50 @@ def make_d_out(x: Inputs, seed: int = 1):
     return raw, None
 
 
+# ---------------------------------------------------------------- response-token log-probabilities
+
+@dataclass(frozen=True)
+class LogprobWorkload:
+    name: str
+    num_tokens: int       # response tokens whose log-probability is needed (all rollouts of a question)
+    hidden_dim: int
+    vocab: int
+    head_std: float = 0.02
+    seed: int = 0
+    note: str = ""
+
+
+LOGPROB_WORKLOADS = {
+    "L1": LogprobWorkload("L1", 333, 512, 5000, head_std=0.05, note="small, ragged in tokens and vocabulary"),
+    "L2": LogprobWorkload("L2", 1000, 3584, 152064, note="7B-shaped LM head, 1,000 tokens"),
+    # the 32K-prefix workload's responses: 8 rollouts x 2,048 response tokens, Qwen2-7B head (d = 3584, V = 152,064)
+    "L3": LogprobWorkload("L3", 8 * 2048, 3584, 152064, note="8 rollouts x 2,048 response tokens, 7B-shaped LM head"),
+}
+
+
+@dataclass
+class LogprobInputs:
+    workload: LogprobWorkload
+    hidden: np.ndarray      # [N, d] fp32 holding bf16-rounded values
+    lm_head: np.ndarray     # [V, d] fp32 holding bf16-rounded values
+    targets: np.ndarray     # [N] int32 sampled token ids
+    bits: dict = field(default_factory=dict)
+
+
+def make_logprob_inputs(w: LogprobWorkload, keep_f32: bool = True) -> LogprobInputs:
+    """hidden ~ N(0,1) (a final-norm output), lm_head ~ N(0, head_std^2), targets uniform; all bf16-rounded.
+    Draw order: hidden, lm_head, targets."""
+    rng = np.random.default_rng(7919 * (w.seed + 1))
+    hb, hv = round_to_bf16(rng.standard_normal((w.num_tokens, w.hidden_dim), dtype=np.float32))
+    wb, wv = round_to_bf16(rng.standard_normal((w.vocab, w.hidden_dim), dtype=np.float32) * np.float32(w.head_std))
+    y = rng.integers(0, w.vocab, size=w.num_tokens).astype(np.int32)
+    return LogprobInputs(w, hv if keep_f32 else None, wv if keep_f32 else None, y, {"hidden": hb, "lm_head": wb})
+
+
+def logprob_flop(w: LogprobWorkload) -> int:
+    return 2 * w.num_tokens * w.hidden_dim * w.vocab
+
+
 # ---------------------------------------------------------------- accounting (measurement only)
 
 def visible_pairs(prefix_len: int, suffix_lens) -> int:
