@@ -186,6 +186,34 @@ int prefix_attn_backward_timed(const prefix_attn_plan_t* plan, const void* q, co
                                void* dv_suffix, void* workspace, size_t workspace_bytes,
                                void* hip_stream, float* kernel_ms);
 
+/* ---- response-token log-probabilities and group advantages (paper Eq. 1 consumes the
+ *      probabilities the policy / old policy / reference model give to the sampled response
+ *      tokens; each device computes the logits of its token slice, Sec. 5.2; Eq. 2 normalises the
+ *      rewards of a group) ---- */
+
+/* For token n with final hidden state h_n, LM-head matrix W and sampled token id y_n:
+ *     z_v = logit_scale * <w_v, h_n>,   LSE_n = ln sum_v exp(z_v),   logprob_n = z_{y_n} - LSE_n,
+ * computed without materialising the [num_tokens, vocab] logits.
+ *   hidden   [num_tokens, hidden_dim] bf16, DEVICE      (hidden_dim a multiple of 64, else
+ *   lm_head  [vocab, hidden_dim]      bf16, DEVICE       PA_ERR_UNSUPPORTED)
+ *   targets  [num_tokens] int32, DEVICE; every id must lie in [0, vocab) (not checked: an id
+ *            outside leaves that token's logprob unspecified)
+ *   logit_scale  1 / sampling temperature, finite and > 0
+ *   logprob_out [num_tokens] fp32; lse_out [num_tokens] fp32 or NULL
+ *   workspace of at least token_logprob_workspace bytes, DEVICE, 16-byte aligned
+ * Enqueues two kernels on `hip_stream` on the current device; allocates nothing. */
+int token_logprob_workspace(int64_t num_tokens, int32_t hidden_dim, int32_t vocab, size_t* workspace_bytes_out);
+int token_logprob_forward(const void* hidden, const void* lm_head, const int32_t* targets,
+                          int64_t num_tokens, int32_t hidden_dim, int32_t vocab, float logit_scale,
+                          float* logprob_out, float* lse_out, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
+
+/* Eq. 2 for num_groups groups of group_size rewards each (DEVICE, fp32, group-major):
+ * A_i = (r_i - mean) / std with the population standard deviation of the group; a group whose
+ * rewards are all equal gets zeros. */
+int grpo_group_advantages(const float* rewards, int32_t group_size, int32_t num_groups,
+                          float* advantages_out, void* hip_stream);
+
 /* Release a plan (NULL is allowed).  Work enqueued with the plan must have finished. */
 void prefix_attn_destroy(prefix_attn_plan_t* plan);
 

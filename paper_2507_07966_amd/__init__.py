@@ -9,7 +9,8 @@ from . import workloads  # noqa: F401
 _BINDING_NAMES = ("PrefixAttnPlan", "PrefixAttnError", "prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed",
                   "prefix_attn_lse", "prefix_attn_destroy", "prefix_attn_status_string",
                   "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_forward_partial",
-                  "prefix_attn_merge_partials",
+                  "prefix_attn_merge_partials", "token_logprob_workspace", "token_logprob_forward",
+                  "grpo_group_advantages",
                   "library_path", "load_library")
 
 

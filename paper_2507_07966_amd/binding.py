@@ -26,6 +26,7 @@ EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forw
                     "prefix_attn_plan_items", "prefix_attn_plan_total_tokens", "prefix_attn_backward_workspace",
                     "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_plan_num_key_items",
                     "prefix_attn_plan_key_items", "prefix_attn_forward_partial", "prefix_attn_merge_partials")
+EXPORTED_SYMBOLS_OTHER = ("token_logprob_workspace", "token_logprob_forward", "grpo_group_advantages")
 
 
 class PrefixAttnError(RuntimeError):
@@ -79,6 +80,13 @@ def load_library():
     lib.prefix_attn_forward_partial.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.c_int32, vp, vp, vp, sz, vp]
     lib.prefix_attn_merge_partials.restype = ctypes.c_int
     lib.prefix_attn_merge_partials.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp]
+    lib.token_logprob_workspace.restype = ctypes.c_int
+    lib.token_logprob_workspace.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.POINTER(sz)]
+    lib.token_logprob_forward.restype = ctypes.c_int
+    lib.token_logprob_forward.argtypes = [vp, vp, vp, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                          vp, vp, vp, sz, vp]
+    lib.grpo_group_advantages.restype = ctypes.c_int
+    lib.grpo_group_advantages.argtypes = [vp, ctypes.c_int32, ctypes.c_int32, vp, vp]
     lib.prefix_attn_backward_workspace.restype = ctypes.c_int
     lib.prefix_attn_backward_workspace.argtypes = [vp, ctypes.POINTER(sz)]
     lib.prefix_attn_backward.restype = ctypes.c_int
@@ -294,6 +302,34 @@ def prefix_attn_backward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_su
     if st:
         raise PrefixAttnError(st, "prefix_attn_backward_timed")
     return float(ms[0]), float(ms[1]), float(ms[2]), float(ms[3])
+
+
+def token_logprob_workspace(num_tokens: int, hidden_dim: int, vocab: int) -> int:
+    n = ctypes.c_size_t()
+    st = load_library().token_logprob_workspace(int(num_tokens), int(hidden_dim), int(vocab), ctypes.byref(n))
+    if st:
+        raise PrefixAttnError(st, "token_logprob_workspace")
+    return int(n.value)
+
+
+def token_logprob_forward(hidden, lm_head, targets, logit_scale, logprob_out, lse_out, workspace, stream=None) -> None:
+    """token_logprob_forward of the C ABI.  hidden [N,d] / lm_head [V,d] bf16 and targets [N] int32 device tensors;
+    logprob_out (and optional lse_out) [N] fp32; workspace uint8 of at least token_logprob_workspace bytes."""
+    N, d = int(hidden.shape[0]), int(hidden.shape[1])
+    V = int(lm_head.shape[0])
+    st = load_library().token_logprob_forward(_ptr(hidden), _ptr(lm_head), _ptr(targets), N, d, V, float(logit_scale),
+                                              _ptr(logprob_out), _ptr(lse_out), _ptr(workspace),
+                                              _nbytes(workspace, 0), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "token_logprob_forward")
+
+
+def grpo_group_advantages(rewards, advantages_out, stream=None) -> None:
+    """grpo_group_advantages of the C ABI.  rewards / advantages_out: [num_groups, group_size] fp32 device tensors."""
+    st = load_library().grpo_group_advantages(_ptr(rewards), int(rewards.shape[1]), int(rewards.shape[0]),
+                                              _ptr(advantages_out), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "grpo_group_advantages")
 
 
 def prefix_attn_destroy(plan: PrefixAttnPlan) -> None:

@@ -13,7 +13,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libprefix_attn.so")
 SOURCES = ["plan.cpp", "api.cpp", "attn_bf16.hip", "attn_f32.hip", "vt_image.hip", "merge.hip",
-           "bwd_api.cpp", "bwd_prep.hip", "bwd_dq_bf16.hip", "bwd_dkv_bf16.hip", "bwd_f32.hip"]
+           "bwd_api.cpp", "bwd_prep.hip", "bwd_dq_bf16.hip", "bwd_dkv_bf16.hip", "bwd_f32.hip",
+           "logprob_api.cpp", "logprob.hip"]
 # packed-fp32 code generation is switched off for every device translation unit
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                 # MFMA results in ordinary vector registers; kernels that need more than 256 registers keep

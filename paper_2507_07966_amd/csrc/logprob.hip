@@ -1,0 +1,256 @@
+// Response-token log-probabilities: logp_n = z_{y_n} - ln sum_v exp(z_v), z = logit_scale * W h_n,
+// without ever materialising the [tokens, vocabulary] logits.
+//
+// The GRPO objective (paper Eq. 1) needs the probabilities the policy, the old policy and the
+// reference model give to the sampled response tokens; after the prefill each device computes the
+// logits of its token slice (Sec. 5.2).  With a 7B-class model that is a [N, 3584] x [3584, 152064]
+// product per model, 1.8e13 FLOP for 16K response tokens, and the logits (10 GB in fp32) are only
+// ever reduced to two numbers per token.
+//
+// Kernel 1 (bf16 MFMA GEMM with a reducing epilogue).  A workgroup (8 wavefronts) computes one
+// 256-vocabulary x 256-token tile of Z^T = W H^T: wavefront (wv, wt) owns 64 vocabulary rows x 128
+// tokens (2 x 4 accumulator blocks of v_mfma_f32_32x32x16_bf16, 128 registers).  W and H panels of
+// 64 channels go global -> LDS through range-checked buffer loads (rows past the end of either
+// matrix read as zero), double buffered, one barrier per 64 channels; 6 LDS operand reads feed 8
+// MFMAs.  In the epilogue every lane holds 32 logits of each of 4 tokens: it reduces them to a
+// maximum and a sum of exponentials, combines with the lane holding the other 32 rows, and writes
+// one (m, l) pair per (wavefront row block, token); the lane that holds the target's logit writes
+// it out.  Workgroups are numbered so that the 32 tiles running together on one XCD form an
+// 8-token-tile x 4-vocabulary-tile block: 12 distinct panels per step share that XCD's L2
+// instead of 64.
+// Kernel 2 combines the (m, l) pairs of a token over all vocabulary blocks: LSE = m + ln l,
+// logp = z_target - LSE.
+#include <hip/hip_runtime.h>
+
+#include "logprob.h"
+#include "mfma_tiles.h"
+
+namespace pa {
+namespace {
+
+using namespace mt;
+
+constexpr int LP_WAVES = 8, LP_THREADS = LP_WAVES * 64;
+constexpr int BK = 64;                      // channels per stage
+constexpr int PANEL_BYTES = LP_TILE * BK * 2;  // one 256-row x 64-channel panel
+constexpr int LP_STAGE = 2 * PANEL_BYTES;      // W panel, H panel
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
+
+// Lane l and lane l ^ 32 hold the two halves of a token's column: both values, via
+// v_permlane32_swap (results read through named temporaries, see attn_bf16.hip).
+__device__ inline void pair_values(float x, float& a, float& b) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  const unsigned r0 = r[0], r1 = r[1];
+  a = __uint_as_float(r0);
+  b = __uint_as_float(r1);
+}
+
+__global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
+    const __bf16* __restrict__ hidden, const __bf16* __restrict__ lm_head, const int32_t* __restrict__ targets,
+    float2* __restrict__ partials, float* __restrict__ target_logit, int64_t N, int d, int V, int TM, int TV,
+    int by_tm, float logit_scale) {
+  __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * LP_STAGE];
+
+  // ---- which tile: XCD x = blockIdx % 8 owns a slice of the token tiles (or, with fewer than 8
+  //      token tiles, of the vocabulary tiles) and walks it in 8 x 4 blocks of tiles
+  int tm, tv;
+  {
+    const int n = blockIdx.x, x = n & 7, j = n >> 3;
+    if (by_tm) {
+      const int mine = (TM - x + 7) / 8;          // token tiles tm = x + 8 k, k < mine
+      const int ngm = ((TM + 7) / 8 + 7) / 8;     // groups of 8 owned token tiles (same for every XCD)
+      const int g = j / 32, i = j % 32;
+      const int k = (g % ngm) * 8 + (i & 7);
+      tv = (g / ngm) * 4 + (i >> 3);
+      tm = x + 8 * k;
+      if (k >= mine || tv >= TV) return;
+    } else {
+      tm = j % TM;
+      tv = x + 8 * (j / TM);
+      if (tv >= TV) return;
+    }
+  }
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int wv = wave & 3, wt = wave >> 2;
+  const int64_t v0 = (int64_t)tv * LP_TILE, t0 = (int64_t)tm * LP_TILE;
+
+  // ---- loads: a panel is 256 rows x 128 bytes = 32 blocks of 1 KiB (8 rows each), 4 per wavefront
+  const int64_t rowb = (int64_t)d * 2;
+  const int64_t w_rows = V - v0 < LP_TILE ? V - v0 : LP_TILE, h_rows = N - t0 < LP_TILE ? N - t0 : LP_TILE;
+  const rsrc_t r_w = make_rsrc(lm_head + v0 * d, w_rows * rowb);
+  const rsrc_t r_h = make_rsrc(hidden + t0 * d, h_rows * rowb);
+  unsigned loff[4];
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+    const int row = (wave * 4 + n) * 8 + lane / 8;
+    const int chunk = (lane % 8) ^ swizzle_term(row, 128);  // logical chunk stored at this position
+    loff[n] = (unsigned)(row * rowb + chunk * 16);
+  }
+  auto issue = [&](int stage, int buf) {
+    unsigned char* dst = smem + buf * LP_STAGE;
+    const unsigned k_off = (unsigned)stage * (BK * 2);
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_w, (PA_LDS_PTR(void))(dst + (wave * 4 + n) * 1024), 16, loff[n], k_off, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(r_h, (PA_LDS_PTR(void))(dst + PANEL_BYTES + (wave * 4 + n) * 1024), 16,
+                                               loff[n], k_off, 0, 0);
+    }
+  };
+
+  f32x16 C[2][4];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) C[a][b][i] = 0.f;
+
+  int ooff[BK / 16];
+#pragma unroll
+  for (int kk = 0; kk < BK / 16; ++kk) ooff[kk] = row_operand_offset<BK>(l32, hf, kk);
+
+  const int nstages = (d + BK - 1) / BK;  // channels past d read as zero (range-checked loads)
+  issue(0, 0);
+  for (int s = 0; s < nstages; ++s) {
+    const int buf = s & 1;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of stage s has landed
+    __syncthreads();                      // everyone's share has; the other buffer is no longer read
+    if (s + 1 < nstages) issue(s + 1, buf ^ 1);
+    const unsigned char* wp = smem + buf * LP_STAGE + (wv * 64) * 128;
+    const unsigned char* hp = smem + buf * LP_STAGE + PANEL_BYTES + (wt * 128) * 128;
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      bf16x8 wa[2], hb[4];
+#pragma unroll
+      for (int a = 0; a < 2; ++a) wa[a] = lds_operand(wp + a * 32 * 128 + ooff[kk]);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) hb[b] = lds_operand(hp + b * 32 * 128 + ooff[kk]);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) C[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[b], C[a][b], 0, 0, 0);
+    }
+  }
+
+  // ---- epilogue.  Register i of C[a][b]: vocabulary row v0 + wv*64 + a*32 + 8*(i/4) + 4*hf + i%4,
+  //      token t0 + wt*128 + b*32 + l32.
+  const float c2 = logit_scale * LOG2E;  // work in base 2
+  const int64_t part_row = ((int64_t)tv * 4 + wv) * N;
+#pragma unroll
+  for (int b = 0; b < 4; ++b) {
+    const int64_t tok = t0 + wt * 128 + b * 32 + l32;
+    float m = -INFINITY;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int64_t vrow = v0 + wv * 64 + a * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
+        if (vrow < V) m = fmaxf(m, C[a][b][i]);
+      }
+    {
+      float u, w2;
+      pair_values(m, u, w2);
+      m = fmaxf(u, w2) * c2;  // -inf only when none of the block's 64 rows exists
+    }
+    float l = 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int64_t vrow = v0 + wv * 64 + a * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
+        if (vrow < V) l += __builtin_amdgcn_exp2f(__builtin_fmaf(C[a][b][i], c2, -m));
+      }
+    {
+      float u, w2;
+      pair_values(l, u, w2);
+      l = u + w2;
+    }
+    const bool block_exists = v0 + wv * 64 < V;
+    if (tok < N) {
+      if (hf == 0) partials[part_row + tok] = block_exists ? float2{m * LN2, l} : float2{-INFINITY, 0.f};
+      // the target's logit, if it lies in this wavefront's 64 rows and this lane's half
+      const int64_t rel = (int64_t)targets[tok] - (v0 + wv * 64);
+      if (rel >= 0 && rel < 64) {
+        const int r = (int)rel & 31, a_t = (int)rel >> 5;
+        if (((r >> 2) & 1) == hf) {
+          const int i_t = 4 * (r >> 3) + (r & 3);
+          float z = 0.f;
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+              if (a == a_t && i == i_t) z = C[a][b][i];
+          target_logit[tok] = z * logit_scale;
+        }
+      }
+    }
+  }
+}
+
+// (m, l) pairs of a token over all vocabulary blocks -> LSE and log-probability.
+__global__ __launch_bounds__(256) void logprob_finalize_kernel(const float2* __restrict__ partials,
+                                                               const float* __restrict__ target_logit,
+                                                               float* __restrict__ logprob, float* __restrict__ lse_out,
+                                                               int64_t N, int nparts) {
+  const int64_t tok = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (tok >= N) return;
+  float m = -INFINITY;
+  for (int p = 0; p < nparts; ++p) m = fmaxf(m, partials[(int64_t)p * N + tok].x);
+  float l = 0.f;
+  for (int p = 0; p < nparts; ++p) {
+    const float2 v = partials[(int64_t)p * N + tok];
+    l += v.y * expf(v.x - m);
+  }
+  const float lse = m + logf(l);
+  logprob[tok] = target_logit[tok] - lse;
+  if (lse_out) lse_out[tok] = lse;
+}
+
+// Eq. 2: A_i = (r_i - mean) / std over one group of G rewards (population std; equal rewards -> 0).
+__global__ __launch_bounds__(64) void group_advantages_kernel(const float* __restrict__ rewards,
+                                                              float* __restrict__ adv, int G, int num_groups) {
+  const int g = blockIdx.x * 64 + threadIdx.x;
+  if (g >= num_groups) return;
+  const float* r = rewards + (int64_t)g * G;
+  float mean = 0.f;
+  for (int i = 0; i < G; ++i) mean += r[i];
+  mean /= (float)G;
+  float var = 0.f;
+  for (int i = 0; i < G; ++i) var += (r[i] - mean) * (r[i] - mean);
+  const float sd = sqrtf(var / (float)G);
+  for (int i = 0; i < G; ++i) adv[(int64_t)g * G + i] = sd > 0.f ? (r[i] - mean) / sd : 0.f;
+}
+
+}  // namespace
+
+int launch_logprob(const LogprobArgs& a, void* stream) {
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int TM = (int)((a.N + LP_TILE - 1) / LP_TILE), TV = (a.V + LP_TILE - 1) / LP_TILE;
+  const int by_tm = TM >= 8;
+  int64_t grid;
+  if (by_tm) {
+    const int ngm = ((TM + 7) / 8 + 7) / 8;
+    grid = (int64_t)8 * 32 * ngm * ((TV + 3) / 4);
+  } else {
+    grid = (int64_t)8 * TM * ((TV + 7) / 8);
+  }
+  logprob_tile_kernel<<<(unsigned)grid, LP_THREADS, 0, s>>>(
+      static_cast<const __bf16*>(a.hidden), static_cast<const __bf16*>(a.lm_head), a.targets,
+      reinterpret_cast<float2*>(a.partials), a.target_logit, a.N, a.d, a.V, TM, TV, by_tm, a.logit_scale);
+  if (hipGetLastError() != hipSuccess) return 1;
+  logprob_finalize_kernel<<<(unsigned)((a.N + 255) / 256), 256, 0, s>>>(
+      reinterpret_cast<const float2*>(a.partials), a.target_logit, a.logprob, a.lse, a.N, TV * 4);
+  return (int)hipGetLastError();
+}
+
+int launch_group_advantages(const float* rewards, float* adv, int G, int num_groups, void* stream) {
+  if (num_groups == 0) return 0;
+  group_advantages_kernel<<<(unsigned)((num_groups + 63) / 64), 64, 0, static_cast<hipStream_t>(stream)>>>(
+      rewards, adv, G, num_groups);
+  return (int)hipGetLastError();
+}
+
+}  // namespace pa

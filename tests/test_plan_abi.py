@@ -17,12 +17,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "prefix_attn.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(prefix_attn_\w+)\s*\(", header))
+    declared = set(re.findall(r"\b((?:prefix_attn|token_logprob|grpo)_\w+)\s*\(", header))
     assert {"prefix_attn_plan", "prefix_attn_forward", "prefix_attn_lse", "prefix_attn_destroy"} <= declared
     lib = ctypes.CDLL(binding.library_path())
     for name in declared:
         assert hasattr(lib, name), name
-    assert declared == set(binding.EXPORTED_SYMBOLS)
+    assert declared == set(binding.EXPORTED_SYMBOLS) | set(binding.EXPORTED_SYMBOLS_OTHER)
 
 
 def host_plan(**kw):
@@ -240,3 +240,22 @@ def test_sharded_calls_check_arguments():
     odd = (ctypes.c_void_p * 2)(a, a + 8)
     assert mp(2, ptrs, odd) == 4
     assert mp(3) == 3 and mp(3, lse=None) == 3                        # host-only plan cannot launch
+
+
+def test_logprob_calls_check_arguments():
+    lib = binding.load_library()
+    a = 0x10000
+    assert pa.token_logprob_workspace(1000, 3584, 152064) >= 4 * 594 * 1000 * 8 + 1000 * 4
+    n = ctypes.c_size_t()
+    assert lib.token_logprob_workspace(0, 64, 10, ctypes.byref(n)) == 2
+    assert lib.token_logprob_workspace(5, 100, 10, ctypes.byref(n)) == 3          # hidden_dim not a multiple of 64
+    assert lib.token_logprob_workspace(5, 64, 10, None) == 1
+    big = pa.token_logprob_workspace(5, 64, 10)
+    f = lambda *p: lib.token_logprob_forward(*p)
+    assert f(None, a, a, 5, 64, 10, 1.0, a, None, a, big, None) == 1
+    assert f(a, a, a, 5, 64, 10, 0.0, a, None, a, big, None) == 2
+    assert f(a, a, a, 5, 64, 10, float("nan"), a, None, a, big, None) == 2
+    assert f(a, a + 2, a, 5, 64, 10, 1.0, a, None, a, big, None) == 4
+    assert f(a, a, a, 5, 64, 10, 1.0, a, None, a, big - 1, None) == 5
+    assert lib.grpo_group_advantages(None, 8, 1, a, None) == 1
+    assert lib.grpo_group_advantages(a, 0, 1, a, None) == 2
