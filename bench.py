@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--prefix-shards", type=int, default=0,
                     help="n > 0: time what ONE device of an n-way prefix-key-sharded group computes (its shard's "
                          "partial pass + the n-way merge); the exchange of partials between devices is not part of it")
+    ap.add_argument("--logprob", default="", metavar="L3",
+                    help="time the response-token log-probability path on this log-prob workload instead")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -81,6 +83,9 @@ def main():
         sys.exit(1)
     pa.load_library()   # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+
+    if args.logprob:
+        return logprob_main(args, pa, wl, torch)
 
     w = wl.WORKLOADS[args.workload]
     x = wl.make_inputs(w)
@@ -212,6 +217,61 @@ def main():
         result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - o_ref).max()),
                                       "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
                                       "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
+    print(json.dumps(result), flush=True)
+
+
+def logprob_main(args, pa, wl, torch):
+    """One "step" = token_logprob_forward (LM-head GEMM tile kernel + finalize) for all response tokens of one
+    question's rollouts under ONE model, inputs resident in HBM.  metric: 2 N d V / time."""
+    w = wl.LOGPROB_WORKLOADS[args.logprob]
+    x = wl.make_logprob_inputs(w)
+    h = torch.from_numpy(x.bits["hidden"].view(np.int16)).cuda().view(torch.bfloat16)
+    W = torch.from_numpy(x.bits["lm_head"].view(np.int16)).cuda().view(torch.bfloat16)
+    y = torch.from_numpy(x.targets).cuda()
+    N, d, V = w.num_tokens, w.hidden_dim, w.vocab
+    ws = torch.empty(pa.token_logprob_workspace(N, d, V), dtype=torch.uint8, device="cuda")
+    lp = torch.empty(N, dtype=torch.float32, device="cuda")
+    lse = torch.empty(N, dtype=torch.float32, device="cuda")
+    for _ in range(args.warmup):
+        pa.token_logprob_forward(h, W, y, 1.0, lp, lse, ws)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        pa.token_logprob_forward(h, W, y, 1.0, lp, lse, ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = float(e0.elapsed_time(e1) / args.steps)
+    flop = wl.logprob_flop(w)
+    tflops = flop / (ms * 1e-3) * 1e-12
+    result = {
+        "metric": "LM-head log-probability TFLOP/s", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.note}", "num_tokens": N, "hidden_dim": d, "vocab": V},
+        "tokens_per_s": round(N / (ms * 1e-3), 1), "flop": flop,
+        # the tile kernel is all but the microseconds of the finalize kernel
+        "roofline": {"kernel": "logprob_tile", "bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
+                     "traffic": measured_traffic(w.name, "logprob_tile")},
+    }
+    if args.calibrate_copy:
+        calibrate_copy(torch)
+    if not args.no_cpu_baseline:
+        from oracle import ref_logprob
+        idx = np.sort(np.random.default_rng(4).choice(N, size=min(N, 64), replace=False))
+        t0 = time.perf_counter()
+        rp, rl = ref_logprob.token_logprobs(x.hidden[idx], x.lm_head, x.targets[idx], 1.0)
+        t_cpu = time.perf_counter() - t0
+        try:
+            cores = len(os.sched_getaffinity(0))
+        except AttributeError:
+            cores = os.cpu_count()
+        got = lp[torch.from_numpy(idx).cuda()].cpu().numpy().astype(np.float64)
+        result["cpu_baseline"] = {"value": round(2 * len(idx) * d * V / t_cpu * 1e-12, 6), "unit": "TFLOP/s",
+                                  "cores": int(cores), "kind": "oracle",
+                                  "sample": f"{len(idx)} seeded tokens against the whole vocabulary (fp64 numpy, {t_cpu:.1f} s)"}
+        result["parity_on_sample"] = {"logprob_max_abs": float(np.abs(got - rp).max())}
     print(json.dumps(result), flush=True)
 
 

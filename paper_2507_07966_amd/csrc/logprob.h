@@ -13,7 +13,7 @@ struct LogprobArgs {
   const int32_t* targets;  // [N]
   float* logprob;          // [N]
   float* lse;              // [N] or null
-  float* partials;         // workspace: [4 * ceil(V / LP_TILE)][N] pairs (m, l)
+  float* partials;         // workspace: [ceil(V / LP_TILE)][N] pairs (m, l)
   float* target_logit;     // workspace: [N]
   int64_t N;
   int32_t d, V;

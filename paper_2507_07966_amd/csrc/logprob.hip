@@ -13,9 +13,9 @@
 // 64 channels go global -> LDS through range-checked buffer loads (rows past the end of either
 // matrix read as zero), double buffered, one barrier per 64 channels; 6 LDS operand reads feed 8
 // MFMAs.  In the epilogue every lane holds 32 logits of each of 4 tokens: it reduces them to a
-// maximum and a sum of exponentials, combines with the lane holding the other 32 rows, and writes
-// one (m, l) pair per (wavefront row block, token); the lane that holds the target's logit writes
-// it out.  Workgroups are numbered so that the 32 tiles running together on one XCD form an
+// maximum and a sum of exponentials, combines with the lane holding the other 32 rows and, through
+// LDS, with the other three row blocks, so the tile writes one (m, l) pair per token; the lane that
+// holds the target's logit writes it out.  Workgroups are numbered so that the 32 tiles running together on one XCD form an
 // 8-token-tile x 4-vocabulary-tile block: 12 distinct panels per step share that XCD's L2
 // instead of 64.
 // Kernel 2 combines the (m, l) pairs of a token over all vocabulary blocks: LSE = m + ln l,
@@ -138,7 +138,8 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
   // ---- epilogue.  Register i of C[a][b]: vocabulary row v0 + wv*64 + a*32 + 8*(i/4) + 4*hf + i%4,
   //      token t0 + wt*128 + b*32 + l32.
   const float c2 = logit_scale * LOG2E;  // work in base 2
-  const int64_t part_row = ((int64_t)tv * 4 + wv) * N;
+  __syncthreads();                        // every wavefront is done with the panels: reuse the LDS
+  float2* stage_ml = reinterpret_cast<float2*>(smem);  // [4 row blocks][256 tokens] (m in base-2 units, l)
 #pragma unroll
   for (int b = 0; b < 4; ++b) {
     const int64_t tok = t0 + wt * 128 + b * 32 + l32;
@@ -168,9 +169,8 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
       pair_values(l, u, w2);
       l = u + w2;
     }
-    const bool block_exists = v0 + wv * 64 < V;
+    if (hf == 0) stage_ml[wv * LP_TILE + wt * 128 + b * 32 + l32] = float2{m, l};  // m = -inf, l = 0 for a block past V
     if (tok < N) {
-      if (hf == 0) partials[part_row + tok] = block_exists ? float2{m * LN2, l} : float2{-INFINITY, 0.f};
       // the target's logit, if it lies in this wavefront's 64 rows and this lane's half
       const int64_t rel = (int64_t)targets[tok] - (v0 + wv * 64);
       if (rel >= 0 && rel < 64) {
@@ -188,25 +188,55 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
       }
     }
   }
+  // one (m, l) pair per token for the tile's 256 vocabulary rows (block 0 always exists)
+  __syncthreads();
+  if (tid < LP_TILE && t0 + tid < N) {
+    float m = stage_ml[tid].x;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) m = fmaxf(m, stage_ml[k * LP_TILE + tid].x);
+    float l = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2 v = stage_ml[k * LP_TILE + tid];
+      l += v.y * __builtin_amdgcn_exp2f(v.x - m);
+    }
+    partials[(int64_t)tv * N + t0 + tid] = float2{m * LN2, l};
+  }
 }
 
-// (m, l) pairs of a token over all vocabulary blocks -> LSE and log-probability.
+// (m, l) pairs of a token over all vocabulary tiles -> LSE and log-probability.  A block handles
+// 64 tokens; its 4 thread groups each walk every fourth tile with an online combine, then merge.
 __global__ __launch_bounds__(256) void logprob_finalize_kernel(const float2* __restrict__ partials,
                                                                const float* __restrict__ target_logit,
                                                                float* __restrict__ logprob, float* __restrict__ lse_out,
                                                                int64_t N, int nparts) {
-  const int64_t tok = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (tok >= N) return;
-  float m = -INFINITY;
-  for (int p = 0; p < nparts; ++p) m = fmaxf(m, partials[(int64_t)p * N + tok].x);
-  float l = 0.f;
-  for (int p = 0; p < nparts; ++p) {
-    const float2 v = partials[(int64_t)p * N + tok];
-    l += v.y * expf(v.x - m);
+  __shared__ float2 sm[4][64];
+  const int tl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int64_t tok = (int64_t)blockIdx.x * 64 + tl;
+  float m = -INFINITY, l = 0.f;
+  if (tok < N)
+    for (int p = grp; p < nparts; p += 4) {
+      const float2 v = partials[(int64_t)p * N + tok];
+      const float mn = fmaxf(m, v.x);
+      l = l * expf(m - mn) + v.y * expf(v.x - mn);  // first term: 0 * exp(-inf) = 0
+      m = mn;
+    }
+  sm[grp][tl] = float2{m, l};
+  __syncthreads();
+  if (grp == 0 && tok < N) {
+    float mm = m;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) mm = fmaxf(mm, sm[k][tl].x);
+    float ll = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float2 v = sm[k][tl];
+      ll += v.y > 0.f ? v.y * expf(v.x - mm) : 0.f;  // a group that saw no tile holds (-inf, 0)
+    }
+    const float lse = mm + logf(ll);
+    logprob[tok] = target_logit[tok] - lse;
+    if (lse_out) lse_out[tok] = lse;
   }
-  const float lse = m + logf(l);
-  logprob[tok] = target_logit[tok] - lse;
-  if (lse_out) lse_out[tok] = lse;
 }
 
 // Eq. 2: A_i = (r_i - mean) / std over one group of G rewards (population std; equal rewards -> 0).
@@ -241,8 +271,8 @@ int launch_logprob(const LogprobArgs& a, void* stream) {
       static_cast<const __bf16*>(a.hidden), static_cast<const __bf16*>(a.lm_head), a.targets,
       reinterpret_cast<float2*>(a.partials), a.target_logit, a.N, a.d, a.V, TM, TV, by_tm, a.logit_scale);
   if (hipGetLastError() != hipSuccess) return 1;
-  logprob_finalize_kernel<<<(unsigned)((a.N + 255) / 256), 256, 0, s>>>(
-      reinterpret_cast<const float2*>(a.partials), a.target_logit, a.logprob, a.lse, a.N, TV * 4);
+  logprob_finalize_kernel<<<(unsigned)((a.N + 63) / 64), 256, 0, s>>>(
+      reinterpret_cast<const float2*>(a.partials), a.target_logit, a.logprob, a.lse, a.N, TV);
   return (int)hipGetLastError();
 }
 

@@ -20,7 +20,7 @@ int check_shape(int64_t N, int32_t d, int32_t V) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 size_t partial_bytes(int64_t N, int32_t V) {
-  const size_t blocks = 4 * (size_t)((V + pa::LP_TILE - 1) / pa::LP_TILE);
+  const size_t blocks = (size_t)((V + pa::LP_TILE - 1) / pa::LP_TILE);
   return align_up(blocks * (size_t)N * 2 * sizeof(float), 256);
 }
 

@@ -26,6 +26,10 @@ def short_name(k: str) -> str:
         return "bwd_prepass"
     if "bwd_dq_f32" in k or "bwd_dkv_f32" in k or "bwd_delta_f32" in k:
         return "backward (fp32) " + ("dq" if "dq" in k else "dkv" if "dkv" in k else "delta")
+    if "logprob_tile_kernel" in k:
+        return "logprob_tile (bf16 MFMA)"
+    if "logprob_finalize" in k:
+        return "logprob_finalize"
     if "pass_f32_kernel" in k:
         return "attention pass (fp32)"
     if "merge_kernel" in k:
