@@ -63,3 +63,50 @@ def test_c2_backward_full_tensor():
     do, bits = wl.make_d_out(x)
     got = run_hip_backward(x, do, bits)
     check_grads(got, oracle_backward(x, do), "bf16", "C2")
+
+
+def test_backward_and_logprob_on_side_stream_and_graph_replay():
+    """Neither call allocates or synchronises, so both can run on any stream and be captured into a HIP graph;
+    every replay must reproduce the eager result bit for bit (stale workspace contents must not matter)."""
+    import torch
+    import paper_2507_07966_amd as pa
+    from tests.gpu_util import run_hip_backward
+    x = wl.make_custom("bf16", 28, 4, 128, 700, (300, 129), seed=9)
+    do, bits = wl.make_d_out(x)
+    eager, (plan, args, grads) = run_hip_backward(x, do, bits, keep=True)
+    bws = args[-1]
+    lpw = wl.make_logprob_inputs(wl.LogprobWorkload("g", 300, 128, 1000, head_std=0.05, seed=2))
+    h = torch.from_numpy(lpw.bits["hidden"].view(np.int16)).cuda().view(torch.bfloat16)
+    W = torch.from_numpy(lpw.bits["lm_head"].view(np.int16)).cuda().view(torch.bfloat16)
+    y = torch.from_numpy(lpw.targets).cuda()
+    lws = torch.empty(pa.token_logprob_workspace(300, 128, 1000), dtype=torch.uint8, device="cuda")
+    lp = torch.zeros(300, dtype=torch.float32, device="cuda")
+    pa.token_logprob_forward(h, W, y, 1.0, lp, None, lws)
+    torch.cuda.synchronize()
+    lp_eager = lp.cpu().numpy().copy()
+
+    def enqueue():
+        pa.prefix_attn_backward(*args)
+        pa.token_logprob_forward(h, W, y, 1.0, lp, None, lws)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()
+    side.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        enqueue()
+    for rep in range(3):
+        for t in grads.values():
+            t.zero_()
+        lp.zero_()
+        bws.random_(0, 255)
+        lws.random_(0, 255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for n in GRAD_NAMES:
+            assert np.array_equal(grads[n].float().cpu().numpy().astype(np.float64), eager[n]), f"replay {rep} {n}"
+        assert np.array_equal(lp.cpu().numpy(), lp_eager), f"replay {rep} logprob"
+    plan.destroy()
