@@ -167,7 +167,8 @@ int prefix_attn_backward_workspace(const prefix_attn_plan_t* plan, size_t* works
  *   workspace           scratch of at least prefix_attn_backward_workspace bytes (the forward
  *                       workspace is not needed and may be reused for it if large enough)
  * Every gradient element is produced by exactly one workgroup in a fixed order (no atomics),
- * so results are bitwise reproducible.  Argument errors are reported before anything is
+ * so results are bitwise reproducible.  bf16 plans with T * (Hq/Hkv) * D * 2 >= 2^31 bytes of
+ * stacked rows per kv head (about 8.4 M token-heads at D = 128) return PA_ERR_UNSUPPORTED.  Argument errors are reported before anything is
  * launched. */
 int prefix_attn_backward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                          const void* v_prefix, const void* k_suffix, const void* v_suffix,

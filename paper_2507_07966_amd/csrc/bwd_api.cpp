@@ -38,6 +38,8 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
       if (misaligned(p)) return PA_ERR_ALIGN;
     }
   if (x.workspace_bytes < plan->bws_bytes) return PA_ERR_WORKSPACE;
+  // the dK/dV pass addresses a kv head's stacked rows with 32-bit byte offsets
+  if (d.dtype == PA_BF16 && plan->Mpad * d.head_dim * 2 >= ((int64_t)1 << 31)) return PA_ERR_UNSUPPORTED;
   if (d.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan
   int cur = -1;
   if (hipGetDevice(&cur) != hipSuccess || cur != d.device) return PA_ERR_HIP;  // the plan's device must be current
