@@ -59,6 +59,9 @@ WORKLOADS = {
     # (P = 0, one sequence of 32,768 video tokens), run once per layer and shared by all rollouts.
     "N1": Workload("N1", "bf16", 28, 4, 128, 0, 64, 0, 1, 32768,
                    note="shared prefix self-attention: 32K video tokens, causal, no rollouts"),
+    # the same for the hour-long video of C4: 3,600 frames x 64 tokens in one causal sequence
+    "N1h": Workload("N1h", "bf16", 28, 4, 128, 0, 64, 0, 1, 230400,
+                    note="shared prefix self-attention of an hour-long video: 230,400 tokens, causal"),
 }
 
 

@@ -59,6 +59,11 @@ def test_n1_prefix_self_attention_sampled_rows():
     sampled_parity("N1", n_random=64, stride=4096)
 
 
+def test_n1h_hour_long_prefix_self_attention_sampled_rows():
+    """230,400 video tokens in one causal sequence (6,300 work items per kv head, 3.8e14 FLOP)."""
+    sampled_parity("N1h", n_random=24, stride=65536)
+
+
 def test_c3_backward_sampled_rows_and_invariants():
     """Backward at the full 32K-prefix size.  dQ is checked on sampled rows the oracle computes one by one.
     dK/dV of a prefix key sum over all 516,096 (row, head) pairs, which the oracle cannot afford here,
