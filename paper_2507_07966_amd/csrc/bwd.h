@@ -20,11 +20,9 @@ struct BwdPrepArgs {
   const float* lse;    // [Hq, T] natural log, as exported after the forward
   float* delta;        // [T, Hq] out: <dO, O>            (fp32 path)
   float* lse_th;       // [T, Hq] out: LSE re-ordered     (fp32 path)
-  // bf16 path only: per kv head, stacked-row copies and transposed tile images
+  // bf16 path only: per kv head, the stacked rows gathered into contiguous order
   void* qs;            // [Hkv][Mpad][D]
   void* dos;           // [Hkv][Mpad][D]
-  void* qst;           // [Hkv][Mpad/64][D][64]
-  void* dost;          // [Hkv][Mpad/64][D][64]
   float* lse2s;        // [Hkv][Mpad]  LSE * log2(e); rows past the end hold a huge value
   float* deltas;       // [Hkv][Mpad]  -<dO, O> per stacked row (negated)
   int32_t* toks;       // [Hkv][Mpad]  packed token index of the stacked row; INT32_MAX past the end
@@ -60,8 +58,6 @@ struct BwdDkvArgs {
   const void* v;
   const void* qs;       // stacked-row copies / images / statistics from the pre-pass
   const void* dos;
-  const void* qst;
-  const void* dost;
   const float* lse2s;
   const float* deltas;
   const int32_t* toks;

@@ -69,8 +69,6 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
   if (bf16) {
     p.qs = ws + plan->boff_qs;
     p.dos = ws + plan->boff_dos;
-    p.qst = ws + plan->boff_qst;
-    p.dost = ws + plan->boff_dost;
     p.lse2s = reinterpret_cast<float*>(ws + plan->boff_lse2s);
     p.deltas = reinterpret_cast<float*>(ws + plan->boff_deltas);
     p.toks = reinterpret_cast<int32_t*>(ws + plan->boff_toks);
@@ -158,8 +156,6 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
   pa::BwdDkvArgs kv{};
   kv.qs = ws + plan->boff_qs;
   kv.dos = ws + plan->boff_dos;
-  kv.qst = ws + plan->boff_qst;
-  kv.dost = ws + plan->boff_dost;
   kv.lse2s = reinterpret_cast<const float*>(ws + plan->boff_lse2s);
   kv.deltas = reinterpret_cast<const float*>(ws + plan->boff_deltas);
   kv.toks = reinterpret_cast<const int32_t*>(ws + plan->boff_toks);

@@ -10,16 +10,19 @@
 //   dW = dO V^T                  (A = dO rows from LDS, B = V in registers)
 //   W  = exp2(c S - LSE log2 e),  dS = W * (dW - delta)   (VALU; the dW accumulator starts from
 //                                                          -delta, read from LDS in register order)
-//   dV^T += dO^T W               (A = transposed dO image, B = W packed to bf16)
-//   dK^T += Q^T dS               (A = transposed Q image,  B = dS packed to bf16)
-// The stacked, row-major Q/dO copies and their transposed images come from the pre-pass; a
-// tile (4 x 16 KiB + statistics) goes global -> LDS with direct-to-LDS loads, double buffered,
-// one barrier per tile.  One wavefront per SIMD (the accumulators, 128 registers, and the K/V
-// columns, 64, need more than half of the register file), so the overlap of MFMA and VALU work
-// is arranged inside the wavefront: see the step stream in the kernel.  Built with the MFMA
-// results in ordinary vector registers (-amdgpu-mfma-vgpr-form): the compiler then keeps the
-// K/V columns in the accumulation registers, which the MFMA reads as B operands directly, and
-// the softmax VALU code needs no register-file copies.
+//   dV^T += dO^T W               (A = dO tile read TRANSPOSED from LDS, B = W packed to bf16)
+//   dK^T += Q^T dS               (A = Q tile read transposed,           B = dS packed to bf16)
+// Q and dO rows of a kv head, gathered into contiguous stacked order by the pre-pass, go
+// global -> LDS with range-checked buffer loads (2 x 16 KiB + statistics per tile), double
+// buffered, one barrier per tile.  The same two row-major tiles serve both kinds of product: read
+// along the rows with 16-byte LDS reads for S and dW, and transposed with ds_read_b64_tr_b16 for
+// dV and dK (two 8-byte transposed reads build one operand); the tile's XOR swizzle is chosen so
+// that both access patterns are bank-conflict free (mfma_tiles.h).  One wavefront per SIMD (the
+// accumulators, 128 registers, and the K/V columns, 64, need more than half of the register
+// file), so MFMA and VALU work is arranged inside the wavefront: see the step stream in the
+// kernel.  Built with the MFMA results in ordinary vector registers (-amdgpu-mfma-vgpr-form): the
+// compiler then keeps the K/V columns in the accumulation registers, which the MFMA reads as B
+// operands directly, and the softmax VALU code needs no register-file copies.
 #include <hip/hip_runtime.h>
 
 #include "bwd.h"
@@ -36,7 +39,7 @@ constexpr float LOG2E = 1.4426950408889634f;
 template <int D, bool CAUSAL>
 __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     const __bf16* __restrict__ k, const __bf16* __restrict__ v, const __bf16* __restrict__ qs,
-    const __bf16* __restrict__ dos, const __bf16* __restrict__ qst, const __bf16* __restrict__ dost,
+    const __bf16* __restrict__ dos,
     const float* __restrict__ lse2s, const float* __restrict__ deltas, const int32_t* __restrict__ toks,
     __bf16* __restrict__ dk,
     __bf16* __restrict__ dv, const KeyItem* __restrict__ items, const int32_t* __restrict__ cu, int64_t T,
@@ -44,7 +47,7 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   using G = Geo<D>;
   constexpr int KK = G::KK, DB = G::DB;
   constexpr int STATS = 1024;  // per row: LSE*log2e, delta, packed token index (3 x 64 words)
-  constexpr int STAGE = 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES + STATS;
+  constexpr int STAGE = 2 * G::ROW_TILE_BYTES + STATS;
   __shared__ __attribute__((aligned(1024))) unsigned char smem[2 * STAGE];
 
   const KeyItem it = items[blockIdx.x];
@@ -73,11 +76,16 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   }
   const float c_log2 = scale * LOG2E;
 
-  int roff[KK], ioff[4];
+  int roff[KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) roff[kk] = row_operand_offset<D>(l32, hf, kk);
+  for (int kk = 0; kk < KK; ++kk) roff[kk] = row_operand_offset_tr<D>(l32, hf, kk);
+  // transposed operands: byte offsets for chunk 0 of every (half, channel block); chunk ch adds 16 rows
+  // (the swizzle term repeats every 16 rows)
+  int troff[2][DB];
 #pragma unroll
-  for (int ch = 0; ch < 4; ++ch) ioff[ch] = image_operand_offset(l32, hf, ch);
+  for (int half = 0; half < 2; ++half)
+#pragma unroll
+    for (int db = 0; db < DB; ++db) troff[half][db] = tr_operand_offset<D>(lane, db, 0, half);
 
   // ---- row tiles: stacked rows M = t * group + j of kv head c, 64 per tile, numbered over all packed tokens
   const int64_t m_begin = CAUSAL ? (int64_t)(off_g + it.key0) * group : 0;
@@ -87,8 +95,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   const int64_t head_rows = (int64_t)it.c * Mpad;
   const __bf16* qs_c = qs + head_rows * D;
   const __bf16* dos_c = dos + head_rows * D;
-  const __bf16* qst_c = qst + head_rows * D;   // image n starts at n * 64 * D elements
-  const __bf16* dost_c = dost + head_rows * D;
   const float* lse_c = lse2s + head_rows;
   const float* del_c = deltas + head_rows;
 
@@ -99,15 +105,15 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
 
   // The loads of a tile are issued in four pieces so they can be spread over the MFMA stream.
   RowTileOffsets<D, KEY_WAVES> lane_off;
-  lane_off.init(D, wave, lane);
-  const rsrc_t r_qs = make_rsrc(qs_c), r_dos = make_rsrc(dos_c), r_qst = make_rsrc(qst_c), r_dost = make_rsrc(dost_c);
+  lane_off.init(D, wave, lane, true);
+  const rsrc_t r_qs = make_rsrc(qs_c), r_dos = make_rsrc(dos_c);
   const rsrc_t r_lse = make_rsrc(lse_c), r_del = make_rsrc(del_c), r_tok = make_rsrc(tok_c);
   auto issue_piece = [&](int tile, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
     const unsigned b0 = (unsigned)tile * (TILE * D * 2);  // byte offset of the tile in each of the four arrays
     if (piece == 0) {
       if (wave == 0) {  // per-row statistics: 64 dwords each, lane l's word lands at word l
-        unsigned char* st = dst + 2 * G::ROW_TILE_BYTES + 2 * G::IMAGE_BYTES;
+        unsigned char* st = dst + 2 * G::ROW_TILE_BYTES;
         const unsigned m4 = (unsigned)tile * (TILE * 4);
         load_dword_to_lds(r_lse, st, lane * 4, m4);
         load_dword_to_lds(r_del, st + TILE * 4, lane * 4, m4);
@@ -116,10 +122,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
       issue_full_row_tile<D, KEY_WAVES>(dst, r_qs, b0, lane_off, wave);
     } else if (piece == 1) {
       issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, r_dos, b0, lane_off, wave);
-    } else if (piece == 2) {
-      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES, r_qst, b0, wave, lane);
-    } else {
-      issue_linear<G::IMAGE_BYTES, KEY_WAVES>(dst + 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES, r_dost, b0, wave, lane);
     }
   };
 
@@ -142,7 +144,7 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
 
   if (tile0 < tile1) {
 #pragma unroll
-    for (int piece = 0; piece < 4; ++piece) issue_piece(tile0, 0, piece);
+    for (int piece = 0; piece < 2; ++piece) issue_piece(tile0, 0, piece);
   }
   for (int tile = tile0; tile < tile1; ++tile) {
     const int buf = (tile - tile0) & 1;
@@ -153,9 +155,7 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     const int next_tile = tile + 1 < tile1 ? tile + 1 : tile;
     const unsigned char* qt = smem + buf * STAGE;
     const unsigned char* dt = qt + G::ROW_TILE_BYTES;
-    const unsigned char* qim = qt + 2 * G::ROW_TILE_BYTES;
-    const unsigned char* dim = qim + G::IMAGE_BYTES;
-    const float* st = reinterpret_cast<const float*>(dim + G::IMAGE_BYTES);
+    const float* st = reinterpret_cast<const float*>(qt + 2 * G::ROW_TILE_BYTES);
 
     f32x16 S[2], W[2];
     bf16x8 Pb[2][2], dSb[2][2];
@@ -173,8 +173,9 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         op1[s] = lds_operand(dt + rb * 32 * G::ROWB + roff[kk]);
       } else {
         const int u = s - NSW, blk = u / (2 * DB), c2 = (u / DB) % 2, db = u % DB;
-        op0[s] = lds_operand(dim + db * 32 * 128 + ioff[2 * blk + c2]);
-        op1[s] = lds_operand(qim + db * 32 * 128 + ioff[2 * blk + c2]);
+        const int chunk_rows = (2 * blk + c2) * 16 * G::ROWB;
+        op0[s] = lds_operand_tr(dt + chunk_rows + troff[0][db], dt + chunk_rows + troff[1][db]);   // dO^T: channels x rows
+        op1[s] = lds_operand_tr(qt + chunk_rows + troff[0][db], qt + chunk_rows + troff[1][db]);   // Q^T
       }
     };
     auto load_stats = [&](int rb, int a) {
@@ -228,7 +229,7 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         dK[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dSb[blk][c2], dK[db], 0, 0, 0);
       }
       // next tile's loads, one piece after each of the first odd steps
-      if ((s & 1) && s < 8) issue_piece(next_tile, buf ^ 1, s >> 1);
+      if ((s & 1) && s < 4) issue_piece(next_tile, buf ^ 1, s >> 1);
       __builtin_amdgcn_sched_barrier(0);
       // softmax slices: block 0 once both blocks' S and dW are complete, block 1 during the first
       // dV/dK steps of block 0; a slice's LSE values are read one slot earlier
@@ -275,7 +276,7 @@ int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream) {
   auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
   const unsigned grid = (unsigned)a.num_items;
 #define PA_LAUNCH(DD, CC)                                                                                        \
-  bwd_dkv_kernel<DD, CC><<<grid, KV_THREADS, 0, s>>>(b(a.k), b(a.v), b(a.qs), b(a.dos), b(a.qst), b(a.dost),     \
+  bwd_dkv_kernel<DD, CC><<<grid, KV_THREADS, 0, s>>>(b(a.k), b(a.v), b(a.qs), b(a.dos),                         \
                                                      a.lse2s, a.deltas, a.toks, static_cast<__bf16*>(a.dk),      \
                                                      static_cast<__bf16*>(a.dv), a.items, a.cu, a.T, a.Mpad,    \
                                                      a.Hkv, a.group, a.scale)

@@ -4,12 +4,9 @@
 // The dK/dV pass walks, per kv head c, the stacked query rows M = t * group + j (t = packed
 // token, j = q head inside the GQA group) in tiles of 64.  For each such tile this kernel writes
 //   - the rows of Q and dO gathered into one contiguous row-major block [64][D],
-//   - their transposed tile images [D][64] in the LDS-ready layout of the MFMA A operand
-//     (columns inside every group of 16 in the order 0-3, 8-11, 4-7, 12-15; 16-byte chunk j of
-//     row d stored at chunk position j ^ ((d >> 1) & 7)),
 //   - per row: LSE * log2(e), -delta and the packed token index.
 // Rows past the last stacked row are zero, with a huge LSE (their weights become exactly 0)
-// and token index INT32_MAX.  Cost: Q, dO and O are read once and Q, dO written twice.
+// and token index INT32_MAX.  Cost: Q, dO and O are read once and Q, dO written once.
 #include <hip/hip_runtime.h>
 
 #include <climits>
@@ -38,33 +35,12 @@ __device__ inline float dot8(u32x4 a, u32x4 b) {
 }
 
 template <int D>
-__device__ inline void emit_image(const unsigned short* t, unsigned short* dst) {
-  constexpr int LD = D + 2;
-  for (int n = threadIdx.x; n < D * 8; n += 256) {
-    const int d = n >> 3, pos = n & 7;
-    const int j = pos ^ ((d >> 1) & 7);  // logical chunk stored at this position
-    u16x8 w;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int s = j * 8 + e;  // column slot
-      const int lo = s & 15;
-      const int rin = (lo & 3) | ((lo & 4) << 1) | ((lo & 8) >> 1);  // swap bits 2 and 3
-      w[e] = t[((s & ~15) + rin) * LD + d];
-    }
-    *reinterpret_cast<u16x8*>(dst + (int64_t)n * 8) = w;
-  }
-}
-
-template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(
     const unsigned short* __restrict__ q, const unsigned short* __restrict__ out,
-    const unsigned short* __restrict__ d_out, const float* __restrict__ lse, unsigned short* __restrict__ qs, unsigned short* __restrict__ dos, unsigned short* __restrict__ qst,
-    unsigned short* __restrict__ dost, float* __restrict__ lse2s, float* __restrict__ deltas,
+    const unsigned short* __restrict__ d_out, const float* __restrict__ lse, unsigned short* __restrict__ qs, unsigned short* __restrict__ dos,
+    float* __restrict__ lse2s, float* __restrict__ deltas,
     int32_t* __restrict__ toks, int64_t T, int64_t Mpad, int Hq, int group) {
-  constexpr int LD = D + 2;   // padded staging row: odd dword stride
   constexpr int CPR = D / 8;  // 16-byte chunks per row
-  __shared__ unsigned short tq[ROWS_PER_ROW_TILE * LD];
-  __shared__ unsigned short tdo[ROWS_PER_ROW_TILE * LD];
   const int64_t tiles_per_head = Mpad / ROWS_PER_ROW_TILE;
   const int c = (int)(blockIdx.x / tiles_per_head);
   const int64_t tile = blockIdx.x - c * tiles_per_head;
@@ -87,13 +63,6 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(
     const int64_t srow = (int64_t)c * Mpad + m;
     *reinterpret_cast<u32x4*>(qs + srow * D + ch * 8) = wq;
     *reinterpret_cast<u32x4*>(dos + srow * D + ch * 8) = wd;
-    unsigned* rq = reinterpret_cast<unsigned*>(tq + row * LD + ch * 8);
-    unsigned* rd = reinterpret_cast<unsigned*>(tdo + row * LD + ch * 8);
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      rq[w] = wq[w];
-      rd[w] = wd[w];
-    }
     // delta: the CPR consecutive lanes of a row add their partial dot products
     float part = dot8(wd, wo);
 #pragma unroll
@@ -104,10 +73,6 @@ __global__ __launch_bounds__(256) void bwd_prep_bf16_kernel(
       toks[srow] = t;
     }
   }
-  __syncthreads();
-  const int64_t image = ((int64_t)c * tiles_per_head + tile) * (D * ROWS_PER_ROW_TILE);
-  emit_image<D>(tq, qst + image);
-  emit_image<D>(tdo, dost + image);
 }
 
 // fp32 path: delta and the LSE in [T, Hq] order, one thread per (token, head) row.
@@ -140,11 +105,11 @@ int launch_bwd_prep(const BwdPrepArgs& a, void* stream) {
   auto w = [](void* p) { return static_cast<unsigned short*>(p); };
   if (a.D == 128)
     bwd_prep_bf16_kernel<128><<<(unsigned)blocks, 256, 0, s>>>(u(a.q), u(a.out), u(a.d_out), a.lse, w(a.qs),
-                                                                w(a.dos), w(a.qst), w(a.dost), a.lse2s, a.deltas,
+                                                                w(a.dos), a.lse2s, a.deltas,
                                                                 a.toks, a.T, a.Mpad, a.Hq, a.group);
   else
     bwd_prep_bf16_kernel<64><<<(unsigned)blocks, 256, 0, s>>>(u(a.q), u(a.out), u(a.d_out), a.lse, w(a.qs),
-                                                               w(a.dos), w(a.qst), w(a.dost), a.lse2s, a.deltas,
+                                                               w(a.dos), a.lse2s, a.deltas,
                                                                a.toks, a.T, a.Mpad, a.Hq, a.group);
   return (int)hipGetLastError();
 }

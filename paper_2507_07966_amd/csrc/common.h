@@ -122,6 +122,6 @@ struct prefix_attn_plan {
   std::vector<pa::KeyItem> key_items[2];
   pa::KeyItem* d_key_items[2] = {nullptr, nullptr};
   int64_t Mpad = 0;                    // stacked rows per kv head, rounded up to ROWS_PER_ROW_TILE
-  size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_qst = 0, boff_dost = 0, boff_lse2s = 0, boff_deltas = 0,
+  size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_lse2s = 0, boff_deltas = 0,
          boff_toks = 0, boff_ktp = 0, boff_kts = 0, bws_bytes = 0;
 };

@@ -40,6 +40,17 @@ constexpr int TILE = 64;  // rows of a row-major tile = columns of a transposed 
 // so 16 consecutive rows read at one logical chunk cover all 64 banks.
 __device__ inline int swizzle_term(int row, int rowb) { return rowb == 256 ? (row & 15) : ((row >> 1) & 7); }
 
+// A second swizzle for row-major tiles that are read both as MFMA operands along the row (16-byte
+// reads, 16 consecutive rows at one logical chunk) and transposed with ds_read_b64_tr_b16 (per
+// 16 lanes: 4 consecutive rows x two 16-byte chunks).  Both patterns are conflict free with
+//   256-byte rows: chunk ^ (((r & 3) << 2) | ((r >> 2) & 3))
+//   128-byte rows: chunk ^ (((L & 1) << 2) | ((L >> 1) & 3)),  L = (r >> 1) & 7.
+__device__ inline int swizzle_term_tr(int row, int rowb) {
+  if (rowb == 256) return ((row & 3) << 2) | ((row >> 2) & 3);
+  const int L = (row >> 1) & 7;
+  return ((L & 1) << 2) | ((L >> 1) & 3);
+}
+
 template <int D>
 struct Geo {
   static constexpr int ROWB = D * 2;            // bytes per row of a row-major tile
@@ -62,6 +73,36 @@ __device__ inline int image_operand_offset(int l32, int hf, int ch) {
 }
 
 __device__ inline bf16x8 lds_operand(const unsigned char* p) { return *reinterpret_cast<const bf16x8*>(p); }
+
+// The same operand offset for a tile stored with swizzle_term_tr.
+template <int D>
+__device__ inline int row_operand_offset_tr(int l32, int hf, int kk) {
+  return l32 * Geo<D>::ROWB + (((2 * kk + hf) ^ swizzle_term_tr(l32, Geo<D>::ROWB)) << 4);
+}
+// Transposed operand from a row-major tile [64 rows][D] stored with swizzle_term_tr: the A operand
+// of a product that contracts over the tile's ROWS.  Lane (l32, hf) receives channel db*32 + l32 and
+// contraction slots e = 0..7 = rows 16*ch + 4*hf + e (e < 4), 16*ch + 8 + 4*hf + (e - 4): the order in
+// which a packed accumulator delivers its rows.  ds_read_b64_tr_b16 hands lane i of a 16-lane group
+// element (i % 4) of the 8 bytes addressed by lanes i/4, i/4 + 4, i/4 + 8, i/4 + 12; so lane s of the
+// group addresses row R0 + s/4, channels Cb + 4*(s % 4) .. +3, and lane i receives channel Cb + i of
+// rows R0 .. R0 + 3.  `lane_byte` is this lane's byte offset for (db = 0, ch = 0, first half).
+template <int D>
+__device__ inline int tr_lane_row(int lane) { return 4 * (lane >> 5) + ((lane & 15) >> 2); }
+template <int D>
+__device__ inline int tr_operand_offset(int lane, int db, int ch, int half) {
+  constexpr int ROWB = Geo<D>::ROWB;
+  const int r = 16 * ch + 8 * half + tr_lane_row<D>(lane);
+  const int c = db * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+  return r * ROWB + (((c >> 3) ^ swizzle_term_tr(r, ROWB)) << 4) + (c & 7) * 2;
+}
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+__device__ inline bf16x8 lds_operand_tr(const unsigned char* lo, const unsigned char* hi) {
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((PA_LDS_PTR(s16x4))lo);
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((PA_LDS_PTR(s16x4))hi);
+  const s16x8 v = {a[0], a[1], a[2], a[3], b[0], b[1], b[2], b[3]};
+  return __builtin_bit_cast(bf16x8, v);
+}
 
 // Direct-to-LDS copy of 1 KiB per wavefront-wide instruction: lane l's 16 bytes land at dst + 16*l.
 __device__ inline void load16_to_lds(const void* src, unsigned char* dst) {
@@ -94,12 +135,13 @@ template <int D, int NW>
 struct RowTileOffsets {
   static constexpr int BLOCKS_PER_WAVE = Geo<D>::ROW_TILE_BYTES / 1024 / NW;
   unsigned off[BLOCKS_PER_WAVE];
-  __device__ inline void init(int64_t row_stride, int wave, int lane) {
+  __device__ inline void init(int64_t row_stride, int wave, int lane, bool tr_swizzle = false) {
     constexpr int ROWB = Geo<D>::ROWB, LANES_PER_ROW = ROWB / 16, ROWS_PER_BLOCK = 1024 / ROWB;
 #pragma unroll
     for (int n = 0; n < BLOCKS_PER_WAVE; ++n) {
       const int row = (wave * BLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
-      const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, ROWB)) * 8;
+      const int swz = tr_swizzle ? swizzle_term_tr(row, ROWB) : swizzle_term(row, ROWB);
+      const int col = ((lane % LANES_PER_ROW) ^ swz) * 8;
       off[n] = (unsigned)((row * row_stride + col) * 2);
     }
   }

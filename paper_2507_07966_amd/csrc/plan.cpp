@@ -125,8 +125,8 @@ void build_key_items(prefix_attn_plan_t& p) {
   });
 }
 
-// Backward workspace: delta and the re-ordered LSE (used by the fp32 path); for bf16 also the stacked Q/dO copies, their
-// transposed images, the per-row statistics and the transposed K images.
+// Backward workspace: delta and the re-ordered LSE (used by the fp32 path); for bf16 also the stacked Q/dO copies, the
+// per-row statistics and the transposed K images.
 void layout_backward_workspace(prefix_attn_plan_t& p) {
   const prefix_attn_desc_t& d = p.desc;
   const size_t rows = (size_t)p.T * d.num_q_heads;
@@ -140,9 +140,7 @@ void layout_backward_workspace(prefix_attn_plan_t& p) {
     const size_t image = (size_t)d.head_dim * pa::KEYS_PER_TILE * 2;
     p.boff_qs = end;
     p.boff_dos = p.boff_qs + stacked;
-    p.boff_qst = p.boff_dos + stacked;
-    p.boff_dost = p.boff_qst + stacked;
-    p.boff_lse2s = p.boff_dost + stacked;
+    p.boff_lse2s = p.boff_dos + stacked;
     p.boff_deltas = p.boff_lse2s + stats;
     p.boff_toks = p.boff_deltas + stats;
     p.boff_ktp = p.boff_toks + stats;

@@ -189,7 +189,7 @@ def test_backward_workspace_and_argument_checks():
     lib = binding.load_library()
     T, Hq, Hkv, D, P = 1152 * 8, 28, 4, 128, 4096
     mpad = -(-T * (Hq // Hkv) // 64) * 64
-    stacked = 4 * Hkv * mpad * D * 2                       # Q, dO row-major and transposed
+    stacked = 2 * Hkv * mpad * D * 2                       # Q and dO gathered into stacked-row order
     images = Hkv * (P // 64 + 8 * (1152 // 64)) * D * 64 * 2
     need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images
     assert need <= plan.backward_workspace_bytes <= need + 12 * 256
