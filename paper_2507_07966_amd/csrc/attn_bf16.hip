@@ -32,19 +32,15 @@
 #include <type_traits>
 
 #include "common.h"
+#include "mfma_tiles.h"
 
 namespace pa {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+using namespace mt;  // vector types, swizzle_term
 
-#define LDS_PTR(T) __attribute__((address_space(3))) T*
-#define GLB_PTR(T) __attribute__((address_space(1))) T*
+#define LDS_PTR(T) PA_LDS_PTR(T)
+#define GLB_PTR(T) PA_GLB_PTR(T)
 
 constexpr int BN = KEYS_PER_TILE;  // keys per LDS tile
 constexpr int NWAVES = ROWS_PER_ITEM / 32;  // one 32-query MFMA block per wavefront
@@ -71,8 +67,6 @@ struct Tile {
   static constexpr int VBLOCKS_PER_WAVE = VBYTES / 1024 / NWAVES;
   static_assert(KBLOCKS_PER_WAVE >= 1 && VBLOCKS_PER_WAVE >= 1, "every wavefront copies at least one block");
 };
-
-__device__ inline int swizzle_term(int row, int rowb) { return rowb == 256 ? (row & 15) : ((row >> 1) & 7); }
 
 // Exchange between lane l and lane l^32 with v_permlane32_swap.  The two results are read
 // through named unsigned temporaries: bit-casting the builtin's vector elements directly was

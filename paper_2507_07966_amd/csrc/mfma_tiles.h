@@ -1,4 +1,4 @@
-// Building blocks of the bf16 MFMA backward kernels (gfx950): vector types, the two LDS tile
+// Building blocks shared by the bf16 MFMA kernels (gfx950): vector types, the two LDS tile
 // layouts with their bank-conflict-free XOR swizzles, direct-to-LDS tile loads and the lane
 // exchange.  Device code only.
 //
@@ -114,7 +114,7 @@ __device__ inline void load16_to_lds(const void* src, unsigned char* dst) {
 // existing row (callers mask what those rows produce).  rows_left >= 1.
 template <int D, int NW>
 __device__ inline void issue_row_tile(unsigned char* dst, const __bf16* first, int64_t row_stride, int rows_left,
-                                      int wave, int lane) {
+                                      int wave, int lane, bool tr_swizzle = false) {
   constexpr int ROWB = Geo<D>::ROWB;
   constexpr int BLOCKS_PER_WAVE = Geo<D>::ROW_TILE_BYTES / 1024 / NW;
   constexpr int LANES_PER_ROW = ROWB / 16, ROWS_PER_BLOCK = 1024 / ROWB;
@@ -123,7 +123,8 @@ __device__ inline void issue_row_tile(unsigned char* dst, const __bf16* first, i
   for (int n = 0; n < BLOCKS_PER_WAVE; ++n) {
     const int blk = wave * BLOCKS_PER_WAVE + n;
     int row = blk * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
-    const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, ROWB)) * 8;  // logical chunk stored at this position
+    const int swz = tr_swizzle ? swizzle_term_tr(row, ROWB) : swizzle_term(row, ROWB);
+    const int col = ((lane % LANES_PER_ROW) ^ swz) * 8;  // logical chunk stored at this position
     row = row < rows_left ? row : rows_left - 1;
     load16_to_lds(first + row * row_stride + col, dst + blk * 1024);
   }
