@@ -95,7 +95,7 @@ def test_c3_backward_sampled_rows_and_invariants():
         rhs = do[:, hs].astype(np.float64).sum((0, 1))
         n_keys = got["dv_prefix"].shape[0] + got["dv_suffix"].shape[0]
         el = max(float(np.sqrt(np.mean(got["dv_prefix"][:, c] ** 2))), float(np.sqrt(np.mean(got["dv_suffix"][:, c] ** 2))))
-        tol = 8 * np.sqrt(n_keys) * u * el          # independent roundings of n_keys outputs, generous factor
+        tol = 16 * np.sqrt(n_keys) * u * el         # independent roundings of n_keys outputs, generous factor
         print(f"C3 backward kv head {c}: |sum dV - sum dO| max {np.abs(lhs - rhs).max():.3e} (tol {tol:.3e}, "
               f"|sum| rms {np.sqrt(np.mean(rhs * rhs)):.3e})", flush=True)
         assert np.sqrt(np.mean(rhs * rhs)) > 20 * tol      # the identity is not vacuous at this tolerance
@@ -108,3 +108,32 @@ def test_c3_backward_sampled_rows_and_invariants():
         tol2 = 8 * u * np.sqrt((qd ** 2).sum() + (kd_p ** 2).sum() + (kd_s ** 2).sum())
         print(f"C3 backward kv head {c}: <q,dq> {a:.4f} <k,dk> {b:.4f} (tol {tol2:.3e})", flush=True)
         assert abs(a - b) <= tol2
+
+
+def test_c5_backward_ragged_sampled_dq_rows_and_value_identity():
+    """Backward at the largest configuration (512K prefix keys, 16 ragged rollouts): dQ on sampled rows against
+    the oracle, and the value-gradient identity sum_keys dV = sum_rows dO on the full tensors."""
+    from tests.gpu_util import GRAD_ABS_RMS, GRAD_MEAN_RMS, GRAD_REL, run_hip_backward
+    w = wl.WORKLOADS["C5"]
+    x = wl.make_inputs(w)
+    do, bits = wl.make_d_out(x)
+    got = run_hip_backward(x, do, bits)
+    for n, a in got.items():
+        assert np.isfinite(a).all(), n
+    rows = wl.sample_rows(x.suffix_lens, w.prompt_len, 1 << 20, 1, seed=13)      # first/last/prompt boundary + 1 random per rollout
+    dq_ref, _ = cref.prefix_shared_attention_backward(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
+                                                      x.suffix_lens, w.scale, do, rows=rows)
+    d = np.abs(got["dq"][rows] - dq_ref)
+    rms = float(np.sqrt(np.mean(dq_ref * dq_ref)))
+    print(f"C5 backward dq on {len(rows)} rows: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (rms {rms:.3e})", flush=True)
+    assert (d <= GRAD_REL["bf16"] * np.abs(dq_ref) + GRAD_ABS_RMS["bf16"] * rms).all()
+    assert d.mean() <= GRAD_MEAN_RMS["bf16"] * rms
+    r = w.num_q_heads // w.num_kv_heads
+    for c in range(w.num_kv_heads):
+        lhs = got["dv_prefix"][:, c].sum(0) + got["dv_suffix"][:, c].sum(0)
+        rhs = do[:, c * r:(c + 1) * r].astype(np.float64).sum((0, 1))
+        n_keys = got["dv_prefix"].shape[0] + got["dv_suffix"].shape[0]
+        el = max(float(np.sqrt(np.mean(got["dv_prefix"][:, c] ** 2))), float(np.sqrt(np.mean(got["dv_suffix"][:, c] ** 2))))
+        tol = 16 * np.sqrt(n_keys) * 2.0 ** -9 * el       # as in the C3 test; the sums themselves are of order 500
+        print(f"C5 backward kv head {c}: |sum dV - sum dO| max {np.abs(lhs - rhs).max():.3e} (tol {tol:.3e})", flush=True)
+        assert np.abs(lhs - rhs).max() <= tol
