@@ -334,6 +334,8 @@ def sharded_main(args, pa, wl, torch, w, x, dev, out, lse):
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(merge_bytes / (t_merge * 1e-3) * 1e-9 / HBM_PEAK_GBS, 4),
                      "traffic": None},
     }
+    if args.calibrate_copy:
+        calibrate_copy(torch)
     if not args.no_cpu_baseline:
         from oracle import cref
         rows = np.sort(wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 2, seed=1))[:64]

@@ -32,6 +32,8 @@ def short_name(k: str) -> str:
         return "logprob_finalize"
     if "pass_f32_kernel" in k:
         return "attention pass (fp32)"
+    if "merge_n_kernel" in k:
+        return "merge_partials (n-way)"
     if "merge_kernel" in k:
         return "merge"
     if "vt_image_kernel" in k:
