@@ -244,3 +244,17 @@ def test_planted_backward_mistakes_fail_the_finite_difference_pin():
     assert differs("k_suffix", good["v_suffix"])
     for n in NAMES:
         assert not differs(n, good[n])
+
+
+@pytest.mark.parametrize("run", IMPLS)
+def test_hand_worked_backward_golden(run):
+    import json
+    import os
+    cases = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked_backward_logprob.json")))["backward_cases"]
+    for c in cases:
+        x = wl.make_custom("f32", 1, 1, 1, 1, c["suffix_lens"], seed=0)
+        for n in NAMES:
+            setattr(x, n, np.array(c[n], dtype=np.float32))
+        got = run(x, np.array(c["d_out"], dtype=np.float32), c["scale"])
+        for n, g in zip(("dq", "dk_prefix", "dv_prefix", "dk_suffix", "dv_suffix"), got):
+            assert np.abs(g - np.array(c[n])).max() < 1e-6, (c["name"], n)     # inputs are fp32-rounded (ln 3 as scale is exact in fp64)

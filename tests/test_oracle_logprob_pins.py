@@ -93,3 +93,13 @@ def test_a1_advantages_hand_worked_and_invariants():
     assert np.allclose(ref.group_advantages(3 * r + 5), a)            # affine rescaling of rewards changes nothing
     assert np.allclose(ref.group_advantages(-r), -a)
     assert (ref.group_advantages([0.5] * 8) == 0).all()               # no signal in a group of equal rewards
+
+
+def test_hand_worked_logprob_golden():
+    import json
+    import os
+    cases = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked_backward_logprob.json")))["logprob_cases"]
+    for c in cases:
+        lp, lse = ref.token_logprobs(np.array(c["hidden"]), np.array(c["lm_head"]), np.array(c["targets"]), c["logit_scale"])
+        assert np.abs(lp - np.array(c["logprob"])).max() < 1e-14, c["name"]
+        assert np.abs(lse - np.array(c["lse"])).max() < 1e-14, c["name"]
