@@ -236,8 +236,10 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
 /* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding
- * entries included: {rollout g (-1 for prefix keys), first key of the block, kv head c (-1 =
- * padding entry), number of keys in the block}. */
+ * entries included; items_out [num_items][6] (HOST): {rollout g (-1 for prefix keys), first key
+ * of the block, kv head c (-1 = padding entry), number of keys in the block, and for prefix
+ * blocks the range [tile0, tile1) of 64-row tiles of the kv head's stacked query rows that the
+ * item streams (a short prefix is split over several items per key block)}. */
 int64_t prefix_attn_plan_num_key_items(const prefix_attn_plan_t* plan, int32_t pass);
 int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 

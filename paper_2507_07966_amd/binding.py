@@ -152,12 +152,13 @@ class PrefixAttnPlan:
         return int(n.value)
 
     def key_items(self, which: int) -> np.ndarray:
-        """dK/dV work list, 0 (prefix key blocks) or 1 (suffix key blocks): int32 [n, 4] = (g, key0, c, nkeys)."""
+        """dK/dV work list, 0 (prefix key blocks) or 1 (suffix key blocks): int32 [n, 6] =
+        (g, key0, c, nkeys, tile0, tile1); [tile0, tile1) is the row-tile range of a prefix item."""
         lib = load_library()
         n = lib.prefix_attn_plan_num_key_items(self.handle, which)
         if n < 0:
             raise PrefixAttnError(2, "prefix_attn_plan_num_key_items")
-        out = np.zeros((n, 4), dtype=np.int32)
+        out = np.zeros((n, 6), dtype=np.int32)
         if n:
             st = lib.prefix_attn_plan_key_items(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
             if st:

@@ -63,9 +63,11 @@ struct BwdDkvArgs {
   const int32_t* toks;
   void* dk;             // same shape as k
   void* dv;
+  float* partial;       // prefix keys with row_splits > 1: fp32 partial gradients [2][row_splits][P][Hkv][D]
   const KeyItem* items;
   const int32_t* cu;
-  int64_t num_items, T, Mpad;
+  int64_t num_items, T, Mpad, P;
+  int32_t row_splits;
   int32_t Hkv, D, group;
   float scale;
   bool causal;          // false: prefix keys; true: a rollout's own keys

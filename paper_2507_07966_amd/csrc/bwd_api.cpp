@@ -166,6 +166,9 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
   kv.D = d.head_dim;
   kv.group = plan->group;
   kv.scale = d.softmax_scale;
+  kv.partial = reinterpret_cast<float*>(ws + plan->boff_part);
+  kv.P = d.prefix_len;
+  kv.row_splits = plan->row_splits;
   if (has_prefix) {
     kv.k = x.k_prefix;
     kv.v = x.v_prefix;

@@ -36,14 +36,19 @@ using namespace mt;
 constexpr int KV_THREADS = KEY_WAVES * 64;
 constexpr float LOG2E = 1.4426950408889634f;
 
-template <int D, bool CAUSAL>
+// PARTIAL (prefix keys of a short prefix): the item streams only the row tiles [tile0, tile1) of its
+// kv head and leaves fp32 partial gradients in `partial` ([2][splits][P][Hkv][D]); a reduction
+// kernel adds the splits.
+template <int D, bool CAUSAL, bool PARTIAL>
 __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     const __bf16* __restrict__ k, const __bf16* __restrict__ v, const __bf16* __restrict__ qs,
     const __bf16* __restrict__ dos,
     const float* __restrict__ lse2s, const float* __restrict__ deltas, const int32_t* __restrict__ toks,
     __bf16* __restrict__ dk,
-    __bf16* __restrict__ dv, const KeyItem* __restrict__ items, const int32_t* __restrict__ cu, int64_t T,
-    int64_t Mpad, int Hkv, int group, float scale) {
+    __bf16* __restrict__ dv, float* __restrict__ partial, int64_t P, int splits,
+    const KeyItem* __restrict__ items, const int32_t* __restrict__ cu, int64_t T, int64_t Mpad, int Hkv, int group,
+    float scale) {
+  static_assert(!(CAUSAL && PARTIAL), "only prefix key blocks are split");
   using G = Geo<D>;
   constexpr int KK = G::KK, DB = G::DB;
   constexpr int STATS = 1024;  // per row: LSE*log2e, delta, packed token index (3 x 64 words)
@@ -90,8 +95,8 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   // ---- row tiles: stacked rows M = t * group + j of kv head c, 64 per tile, numbered over all packed tokens
   const int64_t m_begin = CAUSAL ? (int64_t)(off_g + it.key0) * group : 0;
   const int64_t m_end = CAUSAL ? (int64_t)end_g * group : T * group;
-  const int tile0 = (int)(m_begin / TILE);
-  const int tile1 = (int)((m_end + TILE - 1) / TILE);
+  const int tile0 = CAUSAL ? (int)(m_begin / TILE) : it.tile0;
+  const int tile1 = CAUSAL ? (int)((m_end + TILE - 1) / TILE) : it.tile1;
   const int64_t head_rows = (int64_t)it.c * Mpad;
   const __bf16* qs_c = qs + head_rows * D;
   const __bf16* dos_c = dos + head_rows * D;
@@ -252,7 +257,21 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   }
 
   // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's key
-  if (key_ok) {
+  if (PARTIAL) {
+    if (key_ok) {
+      float* pk = partial + (((int64_t)it.split * P + key) * Hkv + it.c) * D + 4 * hf;
+      float* pv = pk + (int64_t)splits * P * Hkv * D;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const f32x4 wk = {dK[db][4 * a], dK[db][4 * a + 1], dK[db][4 * a + 2], dK[db][4 * a + 3]};
+          const f32x4 wv = {dV[db][4 * a], dV[db][4 * a + 1], dV[db][4 * a + 2], dV[db][4 * a + 3]};
+          *reinterpret_cast<f32x4*>(pk + db * 32 + 8 * a) = wk;
+          *reinterpret_cast<f32x4*>(pv + db * 32 + 8 * a) = wv;
+        }
+    }
+  } else if (key_ok) {
     __bf16* kp = dk + krow * D + 4 * hf;
     __bf16* vp = dv + krow * D + 4 * hf;
 #pragma unroll
@@ -268,6 +287,23 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   }
 }
 
+// Adds the row splits' fp32 partials of the prefix gradients and converts: 4 channels per thread.
+__global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(const float* __restrict__ partial, __bf16* __restrict__ dk,
+                                                             __bf16* __restrict__ dv, int64_t n4, int splits,
+                                                             float scale) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    f32x4 sk = {0.f, 0.f, 0.f, 0.f}, sv = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) {
+      sk += *reinterpret_cast<const f32x4*>(partial + ((int64_t)s * n4 + i) * 4);
+      sv += *reinterpret_cast<const f32x4*>(partial + (((int64_t)splits + s) * n4 + i) * 4);
+    }
+    sk *= scale;
+    *reinterpret_cast<bf16x4*>(dk + i * 4) = __builtin_convertvector(sk, bf16x4);
+    *reinterpret_cast<bf16x4*>(dv + i * 4) = __builtin_convertvector(sv, bf16x4);
+  }
+}
+
 }  // namespace
 
 int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream) {
@@ -275,17 +311,24 @@ int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
   const unsigned grid = (unsigned)a.num_items;
-#define PA_LAUNCH(DD, CC)                                                                                        \
-  bwd_dkv_kernel<DD, CC><<<grid, KV_THREADS, 0, s>>>(b(a.k), b(a.v), b(a.qs), b(a.dos),                         \
-                                                     a.lse2s, a.deltas, a.toks, static_cast<__bf16*>(a.dk),      \
-                                                     static_cast<__bf16*>(a.dv), a.items, a.cu, a.T, a.Mpad,    \
-                                                     a.Hkv, a.group, a.scale)
+  const bool part = !a.causal && a.row_splits > 1;
+#define PA_LAUNCH(DD, CC, PP)                                                                                      \
+  bwd_dkv_kernel<DD, CC, PP><<<grid, KV_THREADS, 0, s>>>(                                                          \
+      b(a.k), b(a.v), b(a.qs), b(a.dos), a.lse2s, a.deltas, a.toks, static_cast<__bf16*>(a.dk),                    \
+      static_cast<__bf16*>(a.dv), a.partial, a.P, a.row_splits, a.items, a.cu, a.T, a.Mpad, a.Hkv, a.group, a.scale)
   if (a.D == 128) {
-    if (a.causal) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
+    if (a.causal) PA_LAUNCH(128, true, false); else if (part) PA_LAUNCH(128, false, true); else PA_LAUNCH(128, false, false);
   } else {
-    if (a.causal) PA_LAUNCH(64, true); else PA_LAUNCH(64, false);
+    if (a.causal) PA_LAUNCH(64, true, false); else if (part) PA_LAUNCH(64, false, true); else PA_LAUNCH(64, false, false);
   }
 #undef PA_LAUNCH
+  if (hipGetLastError() != hipSuccess) return 1;
+  if (part) {
+    const int64_t n4 = a.P * a.Hkv * a.D / 4;
+    const int64_t want = (n4 + 255) / 256;
+    bwd_dkv_reduce_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>(
+        a.partial, static_cast<__bf16*>(a.dk), static_cast<__bf16*>(a.dv), n4, a.row_splits, a.scale);
+  }
   return (int)hipGetLastError();
 }
 

@@ -40,6 +40,10 @@ struct KeyItem {
   int32_t key0;   // first key of the block (prefix index, or position inside the rollout)
   int32_t c;      // kv head
   int32_t nkeys;  // keys in the block (<= KEYS_PER_KEY_ITEM)
+  int32_t tile0;  // prefix blocks: the row tiles [tile0, tile1) of the kv head this item streams
+  int32_t tile1;  //   (a short prefix is split over `row_splits` items per key block to fill the chip)
+  int32_t split;  // prefix blocks: which of the row splits this is
+  int32_t pad_;
 };
 
 // Arguments of one attention pass (prefix or suffix).  All pointers are device pointers.
@@ -122,6 +126,7 @@ struct prefix_attn_plan {
   std::vector<pa::KeyItem> key_items[2];
   pa::KeyItem* d_key_items[2] = {nullptr, nullptr};
   int64_t Mpad = 0;                    // stacked rows per kv head, rounded up to ROWS_PER_ROW_TILE
+  int32_t row_splits = 1;              // items per prefix key block (> 1: fp32 partial gradients are reduced)
   size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_lse2s = 0, boff_deltas = 0,
-         boff_toks = 0, boff_ktp = 0, boff_kts = 0, bws_bytes = 0;
+         boff_toks = 0, boff_ktp = 0, boff_kts = 0, boff_part = 0, bws_bytes = 0;
 };

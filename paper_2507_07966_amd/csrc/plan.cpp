@@ -97,15 +97,30 @@ void build_key_items(prefix_attn_plan_t& p) {
   const int KB = pa::KEYS_PER_KEY_ITEM;
   std::vector<pa::KeyItem>& pre = p.key_items[0];
   pre.clear();
+  p.row_splits = 1;
   if (P > 0) {
+    // A short prefix has few key blocks: split the streamed rows so that about two items per CU
+    // exist, each still streaming at least 64 row tiles.
+    const int64_t row_tiles = p.Mpad / pa::ROWS_PER_ROW_TILE;
+    const int64_t blocks = (int64_t)Hkv * ((P + KB - 1) / KB);
+    int64_t R = (512 + blocks - 1) / blocks;
+    R = std::min<int64_t>(R, std::max<int64_t>(1, row_tiles / 64));
+    R = std::max<int64_t>(1, std::min<int64_t>(R, 16));
+    p.row_splits = (int32_t)R;
+    const int64_t per_split = (row_tiles + R - 1) / R;
     std::vector<std::vector<pa::KeyItem>> per_head(Hkv);
     for (int c = 0; c < Hkv; ++c)
-      for (int key0 = 0; key0 < P; key0 += KB) per_head[c].push_back({-1, key0, c, std::min(KB, P - key0)});
+      for (int key0 = 0; key0 < P; key0 += KB)
+        for (int r = 0; r < (int)R; ++r) {
+          const int32_t t0 = (int32_t)std::min<int64_t>(r * per_split, row_tiles);
+          const int32_t t1 = (int32_t)std::min<int64_t>((r + 1) * per_split, row_tiles);
+          per_head[c].push_back({-1, key0, c, std::min(KB, P - key0), t0, t1, r, 0});
+        }
     const size_t per = per_head[0].size();
     if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
       const int xper = pa::NUM_XCD / Hkv;
       const size_t qlen = (per + xper - 1) / xper;
-      pre.assign(qlen * pa::NUM_XCD, pa::KeyItem{-1, 0, -1, 0});
+      pre.assign(qlen * pa::NUM_XCD, pa::KeyItem{-1, 0, -1, 0, 0, 0, 0, 0});
       for (int x = 0; x < pa::NUM_XCD; ++x) {
         const int c = x / xper, sub = x % xper;
         for (size_t k = 0; k * xper + sub < per; ++k) pre[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
@@ -118,7 +133,8 @@ void build_key_items(prefix_attn_plan_t& p) {
   suf.clear();
   for (int c = 0; c < Hkv; ++c)
     for (int g = 0; g < p.desc.num_rollouts; ++g)
-      for (int key0 = 0; key0 < p.lens[g]; key0 += KB) suf.push_back({g, key0, c, std::min(KB, p.lens[g] - key0)});
+      for (int key0 = 0; key0 < p.lens[g]; key0 += KB)
+        suf.push_back({g, key0, c, std::min(KB, p.lens[g] - key0), 0, 0, 0, 0});
   const std::vector<int32_t>& lens = p.lens;
   std::stable_sort(suf.begin(), suf.end(), [&lens](const pa::KeyItem& a, const pa::KeyItem& b) {
     return lens[a.g] - a.key0 > lens[b.g] - b.key0;
@@ -146,6 +162,9 @@ void layout_backward_workspace(prefix_attn_plan_t& p) {
     p.boff_ktp = p.boff_toks + stats;
     p.boff_kts = p.boff_ktp + align_up((size_t)d.num_kv_heads * p.tiles_prefix * image, 256);
     end = p.boff_kts + align_up((size_t)d.num_kv_heads * p.tiles_suffix * image, 256);
+    p.boff_part = end;  // fp32 partial dK, dV of the prefix per row split: [2][row_splits][P][Hkv][D]
+    if (p.row_splits > 1)
+      end += align_up((size_t)2 * p.row_splits * d.prefix_len * d.num_kv_heads * d.head_dim * sizeof(float), 256);
   }
   p.bws_bytes = end;
 }
@@ -176,6 +195,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     p->group = desc->num_q_heads / desc->num_kv_heads;
     build_prefix_items(*p);
     build_suffix_items(*p);
+    p->Mpad = ((int64_t)p->T * p->group + pa::ROWS_PER_ROW_TILE - 1) / pa::ROWS_PER_ROW_TILE * pa::ROWS_PER_ROW_TILE;
     build_key_items(*p);
   } catch (const std::bad_alloc&) {
     delete p;
@@ -300,10 +320,12 @@ int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int
   if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
   const std::vector<pa::KeyItem>& v = plan->key_items[pass];
   for (size_t n = 0; n < v.size(); ++n) {
-    items_out[4 * n + 0] = v[n].g;
-    items_out[4 * n + 1] = v[n].key0;
-    items_out[4 * n + 2] = v[n].c;
-    items_out[4 * n + 3] = v[n].nkeys;
+    items_out[6 * n + 0] = v[n].g;
+    items_out[6 * n + 1] = v[n].key0;
+    items_out[6 * n + 2] = v[n].c;
+    items_out[6 * n + 3] = v[n].nkeys;
+    items_out[6 * n + 4] = v[n].tile0;
+    items_out[6 * n + 5] = v[n].tile1;
   }
   return PA_OK;
 }

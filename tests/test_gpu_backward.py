@@ -34,6 +34,7 @@ EDGE = [
     ("bf16", 7, 1, 128, 1000, (37,) * 5),            # one GQA group, many short rollouts
     ("bf16", 2, 2, 128, 129, (513,)),                # group = 1, key blocks with a ragged tail
     ("bf16", 6, 2, 128, 200, (130, 127, 1, 129)),    # rollout boundaries inside row tiles and key blocks
+    ("bf16", 8, 2, 64, 300, (1500, 700, 1)),         # short prefix, many rows: prefix key blocks split over row ranges
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),
@@ -49,8 +50,9 @@ def test_backward_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
     check_grads(got, oracle_backward(x, do), dtype, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
 
 
-def test_backward_bitwise_reproducible():
-    x = wl.make_custom("bf16", 28, 4, 128, 500, (300, 129), seed=7)
+@pytest.mark.parametrize("Hq,Hkv,D,P,lens", [(28, 4, 128, 500, (300, 129)), (8, 2, 64, 300, (1500, 700, 1))])
+def test_backward_bitwise_reproducible(Hq, Hkv, D, P, lens):
+    x = wl.make_custom("bf16", Hq, Hkv, D, P, lens, seed=7)
     do, bits = wl.make_d_out(x)
     a = run_hip_backward(x, do, bits)
     b = run_hip_backward(x, do, bits)

@@ -147,16 +147,17 @@ def test_c5_ragged_plan_builds_fast():
 
 # ---------------------------------------------------------------- backward: schedule and argument checks
 
-def key_coverage(plan, Hkv, P, lens):
-    """Every prefix key and every suffix key of every kv head lies in exactly one dK/dV work item."""
-    pre = [np.zeros(P, dtype=np.int32) for _ in range(Hkv)]
-    for g, key0, c, n in plan.key_items(0):
+def key_coverage(plan, Hq, Hkv, P, lens):
+    """Every (prefix key, row tile) pair and every suffix key of every kv head lies in exactly one dK/dV work item."""
+    row_tiles = -(-sum(lens) * (Hq // Hkv) // 64)
+    pre = [np.zeros((P, row_tiles), dtype=np.int32) for _ in range(Hkv)]
+    for g, key0, c, n, t0, t1 in plan.key_items(0):
         if c < 0:
             continue
-        assert g == -1 and 0 < n <= 128 and key0 % 128 == 0 and key0 + n <= P
-        pre[c][key0:key0 + n] += 1
+        assert g == -1 and 0 < n <= 128 and key0 % 128 == 0 and key0 + n <= P and 0 <= t0 <= t1 <= row_tiles
+        pre[c][key0:key0 + n, t0:t1] += 1
     suf = [[np.zeros(S, dtype=np.int32) for S in lens] for _ in range(Hkv)]
-    for g, key0, c, n in plan.key_items(1):
+    for g, key0, c, n, _, _ in plan.key_items(1):
         assert 0 <= g < len(lens) and 0 <= c < Hkv and 0 < n <= 128 and key0 % 128 == 0 and key0 + n <= lens[g]
         suf[c][g][key0:key0 + n] += 1
     for c in range(Hkv):
@@ -170,7 +171,7 @@ def key_coverage(plan, Hkv, P, lens):
 ])
 def test_backward_schedule_covers_every_key_once(Hq, Hkv, P, lens):
     plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
-    key_coverage(plan, Hkv, P, lens)
+    key_coverage(plan, Hq, Hkv, P, lens)
 
 
 def test_backward_items_are_grouped_by_kv_head_per_xcd():
@@ -191,8 +192,13 @@ def test_backward_workspace_and_argument_checks():
     mpad = -(-T * (Hq // Hkv) // 64) * 64
     stacked = 2 * Hkv * mpad * D * 2                       # Q and dO gathered into stacked-row order
     images = Hkv * (P // 64 + 8 * (1152 // 64)) * D * 64 * 2
-    need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images
+    splits = len([1 for it in plan.key_items(0) if it[2] == 0 and it[1] == 0])     # items of one key block
+    assert splits == 4                                                              # 128 key blocks -> 512 items
+    partials = 2 * splits * P * Hkv * D * 4
+    need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images + partials
     assert need <= plan.backward_workspace_bytes <= need + 12 * 256
+    c3 = host_plan(prefix_len=32768, suffix_lens=[2304] * 8)
+    assert len(c3.key_items(0)) == 1024                                             # long prefix: no split
     assert host_plan(dtype="f32").backward_workspace_bytes <= 2 * T * Hq * 4 + 2 * 256
     a = 0x10000
     big = plan.backward_workspace_bytes
