@@ -152,7 +152,8 @@ int prefix_attn_merge_partials(const prefix_attn_plan_t* plan, int32_t n, const 
  * (Sec. 5.1).  The LSE is treated as a saved statistic, not as a differentiated output. */
 
 /* Bytes of backward workspace a plan needs (per-row statistics; for bf16 also re-laid-out
- * copies of Q, dO and K). */
+ * copies of Q, dO and K, and for a short prefix fp32 partial prefix gradients of the row ranges
+ * its key blocks are split over). */
 int prefix_attn_backward_workspace(const prefix_attn_plan_t* plan, size_t* workspace_bytes_out);
 
 /* Enqueue the backward on `hip_stream`.  All tensors are DEVICE pointers, 16-byte aligned, in
