@@ -64,6 +64,9 @@ def main():
                          "partial pass + the n-way merge); the exchange of partials between devices is not part of it")
     ap.add_argument("--logprob", default="", metavar="L3",
                     help="time the response-token log-probability path on this log-prob workload instead")
+    ap.add_argument("--fold-prompt", action="store_true",
+                    help="two-level sharing: the rollouts share their question, so the prompt is computed once and "
+                         "joins the shared prefix (two calls per step); also times the one-call form on the same values")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -86,6 +89,9 @@ def main():
 
     if args.logprob:
         return logprob_main(args, pa, wl, torch)
+
+    if args.fold_prompt:
+        return folded_main(args, pa, wl, torch)
 
     w = wl.WORKLOADS[args.workload]
     x = wl.make_inputs(w)
@@ -218,6 +224,67 @@ def main():
                                       "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
                                       "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
     print(json.dumps(result), flush=True)
+
+
+def folded_main(args, pa, wl, torch):
+    """Forward with the shared question folded into the prefix (prompt call + folded call per step) next to
+    the one-call form on the same shared-prompt values."""
+    w = wl.WORKLOADS[args.workload]
+    x = wl.share_prompt(wl.make_inputs(w))
+    prompt_call, folded_call, _ = wl.fold_prompt(x)
+
+    def prepare(c):
+        cw = c.workload
+        dev = [torch.from_numpy(c.bits[n].view(np.int16)).cuda().view(torch.bfloat16)
+               for n in ("q", "k_prefix", "v_prefix", "k_suffix", "v_suffix")]
+        plan = pa.prefix_attn_plan(cw.num_q_heads, cw.num_kv_heads, cw.head_dim, cw.prefix_len, c.suffix_lens, cw.scale,
+                                   dtype=cw.dtype, device=0)
+        ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
+        out = torch.empty((c.total_suffix, cw.num_q_heads, cw.head_dim), dtype=torch.bfloat16, device="cuda")
+        lse = torch.empty((cw.num_q_heads, c.total_suffix), dtype=torch.float32, device="cuda")
+        return plan, dev, ws, out, lse
+
+    def run(prepared):
+        plan, dev, ws, out, lse = prepared
+        pa.prefix_attn_forward(plan, *dev, out, ws)
+        pa.prefix_attn_lse(plan, ws, lse)
+
+    def timed(calls):
+        for _ in range(args.warmup):
+            for c in calls:
+                run(c)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            for c in calls:
+                run(c)
+        e1.record()
+        torch.cuda.synchronize()
+        return float(e0.elapsed_time(e1) / args.steps)
+
+    two_level = [prepare(prompt_call), prepare(folded_call)]
+    one_call = [prepare(x)]
+    ms_fold = timed(two_level)
+    ms_one = timed(one_call)
+    flop_fold = sum(wl.effective_flop(w.num_q_heads, w.head_dim, c.workload.prefix_len, c.suffix_lens)
+                    for c in (prompt_call, folded_call))
+    flop_one = wl.effective_flop(w.num_q_heads, w.head_dim, w.prefix_len, x.suffix_lens)
+    tflops = flop_fold / (ms_fold * 1e-3) * 1e-12
+    print(json.dumps({
+        "metric": "effective attention TFLOP/s", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_fold, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name} with one question shared by all rollouts, prompt folded into the prefix: "
+                               f"call 1 = {w.prompt_len} prompt tokens over {w.prefix_len} video tokens, call 2 = prefix "
+                               f"{w.prefix_len + w.prompt_len}, {w.num_rollouts} rollouts of response tokens only"},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / MFMA_BF16_PEAK_TFLOPS, 2),
+        "effective_flop": flop_fold,
+        "one_call_form": {"ms_per_step": round(ms_one, 4), "effective_flop": flop_one,
+                          "tflops": round(flop_one / (ms_one * 1e-3) * 1e-12, 2)},
+        "time_saved_pct": round(100 * (1 - ms_fold / ms_one), 2),
+        "flop_saved_pct": round(100 * (1 - flop_fold / flop_one), 2),
+    }), flush=True)
 
 
 def logprob_main(args, pa, wl, torch):

@@ -231,9 +231,12 @@ int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_ite
 /* Number of work items of a pass (0 = prefix pass, 1 = suffix pass), padding items included. */
 int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass);
 
-/* Copy the work list of a pass into items_out [num_items][4] (HOST) in launch order:
+/* Copy the work list of a pass into items_out [num_items][5] (HOST) in launch order:
  * {rollout g (-1 = padding item), first stacked row inside the rollout, kv head c,
- *  number of keys the item sweeps}. */
+ *  number of keys the item sweeps, first key it sweeps}.  A suffix-pass item sweeps the
+ * rollout's keys from 0.  A prefix-pass item sweeps the whole prefix unless the call has so
+ * few rows that the prefix is cut into several key ranges per block of rows (bf16 only);
+ * the ranges of a block are disjoint, cover the prefix, and their partials are merged. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
 /* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding

@@ -53,6 +53,29 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   a.D = d.head_dim;
   a.group = plan->group;
   a.scale = d.softmax_scale;
+  a.part_rows = plan->T * d.num_q_heads;
+  // With key splits the prefix pass leaves `ks` partials in the workspace and an n-way merge
+  // combines them (and the suffix partial) instead of the two-way merge.
+  const int ks = plan->key_splits;
+  auto merge_splits = [&](bool suffix_too, void* dst, int32_t dst_dtype, float* lse_th) {
+    pa::MergeNArgs m{};
+    for (int i = 0; i < ks; ++i) {
+      m.o[i] = o1 + (size_t)i * a.part_rows * d.head_dim;
+      m.lse[i] = lse1 + (size_t)i * a.part_rows;
+    }
+    if (suffix_too) {
+      m.o[ks] = o2;
+      m.lse[ks] = lse2;
+    }
+    m.out = dst;
+    m.lse_th_out = lse_th;
+    m.T = plan->T;
+    m.n = ks + (suffix_too ? 1 : 0);
+    m.Hq = d.num_q_heads;
+    m.D = d.head_dim;
+    m.dtype = dst_dtype;
+    return pa::launch_merge_n(m, hip_stream);
+  };
   auto launch_pass = (d.dtype == PA_BF16) ? pa::launch_pass_bf16 : pa::launch_pass_f32;
 
   hipStream_t hs = static_cast<hipStream_t>(hip_stream);
@@ -80,15 +103,19 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     a.vt = ws + plan->off_vtp;
     a.vt_off = nullptr;
     a.vt_tiles_per_head = plan->tiles_prefix;
-    a.o_part = with_suffix ? o1 : static_cast<float*>(out);  // a prefix-only partial goes straight to the caller
-    a.lse_part = with_suffix ? lse1 : lse_partial;
+    const bool direct = !with_suffix && ks == 1;  // an unsplit prefix-only partial goes straight to the caller
+    a.o_part = direct ? static_cast<float*>(out) : o1;
+    a.lse_part = direct ? lse_partial : lse1;
     a.items = plan->d_items[0];
     a.num_items = (int64_t)plan->items[0].size();
     a.causal = false;
     if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[2], hs) != hipSuccess) return PA_ERR_HIP;
-  if (!with_suffix) return PA_OK;
+  if (!with_suffix) {
+    if (ks > 1 && merge_splits(false, out, PA_F32, lse_partial) != 0) return PA_ERR_HIP;
+    return PA_OK;
+  }
   a.k = k_suffix;
   a.v = v_suffix;
   a.vt = ws + plan->off_vts;
@@ -102,6 +129,12 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 
   if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
+  if (ks > 1) {
+    if (merge_splits(true, out, mode == FULL ? d.dtype : (int32_t)PA_F32, mode == FULL ? lse : lse_partial) != 0)
+      return PA_ERR_HIP;
+    if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
+    return PA_OK;
+  }
   pa::MergeArgs m{};
   m.o1 = o1;
   m.lse1 = lse1;

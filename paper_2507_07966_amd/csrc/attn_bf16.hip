@@ -92,8 +92,8 @@ template <int D, bool CAUSAL>
 __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
     float* __restrict__ o_part, float* __restrict__ lse_part, const WorkItem* __restrict__ items,
-    const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head, int Hq, int Hkv,
-    int group, float scale) {
+    const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head,
+    int64_t part_rows, int Hq, int Hkv, int group, float scale) {
   using TL = Tile<D>;
   constexpr int KK = D / 16;  // contraction steps of QK^T
   constexpr int DB = D / 32;  // 32-channel blocks of the output
@@ -109,8 +109,9 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   const int nrows = S_g * group;
   const int nkeys = it.nkeys;
   const int64_t row_stride = (int64_t)Hkv * D;
-  const __bf16* kbase = k + ((int64_t)(CAUSAL ? off_g : 0) * Hkv + it.c) * D;
-  const __bf16* vtbase = vt + ((int64_t)it.c * vt_tiles_per_head + (CAUSAL ? vt_off[it.g] : 0)) * (D * BN);
+  // prefix pass: the item sweeps prefix keys [key0, key0 + nkeys), key0 a multiple of the tile
+  const __bf16* kbase = k + ((int64_t)(CAUSAL ? off_g : it.key0) * Hkv + it.c) * D;
+  const __bf16* vtbase = vt + ((int64_t)it.c * vt_tiles_per_head + (CAUSAL ? vt_off[it.g] : it.key0 / BN)) * (D * BN);
 
   // ---- this lane's query column
   bf16x8 Q[KK];
@@ -380,7 +381,8 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   const float l = pair_sum(lsum);
   if (orow >= 0) {
     const float inv = 1.0f / l;
-    float* op = o_part + orow * D + 4 * hf;
+    const int64_t prow = (CAUSAL ? 0 : (int64_t)it.split * part_rows) + orow;  // key split s fills partial s
+    float* op = o_part + prow * D + 4 * hf;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -388,7 +390,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
         f32x4 w = {O[db][4 * a] * inv, O[db][4 * a + 1] * inv, O[db][4 * a + 2] * inv, O[db][4 * a + 3] * inv};
         *reinterpret_cast<f32x4*>(op + db * 32 + 8 * a) = w;
       }
-    if (hf == 0) lse_part[orow] = mref * scale + __logf(l);
+    if (hf == 0) lse_part[prow] = mref * scale + __logf(l);
   }
 }
 
@@ -403,7 +405,7 @@ int launch_pass_bf16(const PassArgs& a, void* stream) {
   const unsigned grid = (unsigned)a.num_items;
 #define PA_LAUNCH(DD, CC)                                                                                         \
   pass_bf16_kernel<DD, CC><<<grid, NTHREADS, 0, s>>>(q, k, vt, a.o_part, a.lse_part, a.items, a.cu, a.vt_off, \
-                                                     a.vt_tiles_per_head, a.Hq, a.Hkv, a.group, a.scale)
+                                                     a.vt_tiles_per_head, a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
   if (a.D == 128) {
     if (a.causal) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
   } else {

@@ -18,13 +18,17 @@ namespace pa {
 constexpr int ROWS_PER_ITEM = PA_ROWS_PER_ITEM;
 constexpr int KEYS_PER_TILE = 64;
 constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
+constexpr int NUM_CU = 256;
 
 // One entry of a pass's work list.  g < 0 marks a padding entry (the workgroup exits).
 struct WorkItem {
   int32_t g;      // rollout
   int32_t row0;   // first stacked row inside the rollout, m = i * group + (h % group)
   int32_t c;      // kv head
-  int32_t nkeys;  // keys swept: P in the prefix pass, causal extent in the suffix pass
+  int32_t nkeys;  // keys swept: the item's share of P in the prefix pass, causal extent in the suffix pass
+  int32_t key0;   // prefix pass: first prefix key swept (a multiple of KEYS_PER_TILE); suffix pass: 0
+  int32_t split;  // prefix pass: which key split this is (its partial lands in slot `split`); else 0
+  int32_t pad_[2];
 };
 
 // Backward tile geometry.  The key-stationary pass (dK/dV) gives a workgroup KEYS_PER_KEY_ITEM
@@ -59,6 +63,7 @@ struct PassArgs {
   const int32_t* vt_off;  // [G+1] first tile image of each rollout (suffix pass); null for the prefix pass
   int64_t vt_tiles_per_head;  // tile images per kv head in `vt`
   int64_t num_items;
+  int64_t part_rows;    // T * Hq: rows of one partial (key split s writes slot s of o_part / lse_part)
   int32_t Hq, Hkv, D, group;
   float scale;          // softmax scale
   bool causal;          // false: prefix pass (k/v indexed from 0, no mask); true: suffix pass
@@ -99,6 +104,7 @@ struct MergeNArgs {
   const float* lse[PA_MAX_PARTIALS];
   void* out;        // [T, Hq, D] in `dtype`
   float* lse_out;   // [Hq, T] or null
+  float* lse_th_out;  // [T, Hq] or null
   int64_t T;
   int32_t n, Hq, D, dtype;
 };
@@ -119,6 +125,7 @@ struct prefix_attn_plan {
   int32_t* d_cu = nullptr;             // cu followed by vt_off, one allocation
   int32_t* d_vt_off = nullptr;
   int32_t tiles_prefix = 0, tiles_suffix = 0;
+  int32_t key_splits = 1;              // prefix-pass items per block of rows (> 1: few rows, the prefix keys are split)
   pa::WorkItem* d_items[2] = {nullptr, nullptr};
   // workspace layout, byte offsets
   size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;

@@ -76,9 +76,13 @@ __global__ __launch_bounds__(256) void merge_n_kernel(MergeNArgs a) {
     } else {
       *reinterpret_cast<f32x4*>(static_cast<float*>(a.out) + idx * 4) = r;
     }
-    if (ch == 0 && a.lse_out) {
-      const int64_t t = row / a.Hq, h = row - t * a.Hq;
-      a.lse_out[h * a.T + t] = m + logf(tot);
+    if (ch == 0) {
+      const float l = m + logf(tot);
+      if (a.lse_out) {
+        const int64_t t = row / a.Hq, h = row - t * a.Hq;
+        a.lse_out[h * a.T + t] = l;
+      }
+      if (a.lse_th_out) a.lse_th_out[row] = l;
     }
   }
 }

@@ -44,23 +44,44 @@ int validate(const prefix_attn_desc_t* d) {
 // runs on XCD n % 8 and each XCD has a private L2, so the list is interleaved such that one kv
 // head's items land on a fixed subset of XCDs and walk the prefix K/V tiles together: the
 // tiles are then fetched from HBM about once per XCD subset instead of once per workgroup.
+//
+// A call with few rows (a short prompt over a long video, say) has fewer row blocks than the
+// chip has CUs.  The prefix keys are then cut into `key_splits` contiguous ranges of whole
+// tiles, one item per (row block, range), each leaving its own fp32 partial; the merge combines
+// them with the suffix partial.  Items of one range are adjacent so they share its tiles in L2.
 void build_prefix_items(prefix_attn_plan_t& p) {
   std::vector<WorkItem>& out = p.items[0];
   out.clear();
+  p.key_splits = 1;
   const int Hkv = p.desc.num_kv_heads;
   const int P = (int)p.desc.prefix_len;
   if (P == 0) return;
+  int64_t blocks = 0;
+  for (int g = 0; g < p.desc.num_rollouts; ++g)
+    blocks += ((int64_t)p.lens[g] * p.group + pa::ROWS_PER_ITEM - 1) / pa::ROWS_PER_ITEM;
+  blocks *= Hkv;
+  if (p.desc.dtype == PA_BF16) {  // one round of workgroups, at least 8 tiles per range
+    const int64_t fit = pa::NUM_CU / blocks, by_len = p.tiles_prefix / 8;
+    p.key_splits = (int32_t)std::max<int64_t>(1, std::min<int64_t>({fit, by_len, PA_MAX_PARTIALS - 1}));
+  }
+  const int KS = p.key_splits;
+  const int tiles_per_split = (p.tiles_prefix + KS - 1) / KS;
   std::vector<std::vector<WorkItem>> per_head(Hkv);
   for (int c = 0; c < Hkv; ++c)
-    for (int g = 0; g < p.desc.num_rollouts; ++g) {
-      const int nrows = p.lens[g] * p.group;
-      for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM) per_head[c].push_back({g, row0, c, P});
+    for (int s = 0; s < KS; ++s) {
+      const int key0 = std::min(s * tiles_per_split * pa::KEYS_PER_TILE, P);
+      const int key1 = std::min((s + 1) * tiles_per_split * pa::KEYS_PER_TILE, P);
+      for (int g = 0; g < p.desc.num_rollouts; ++g) {
+        const int nrows = p.lens[g] * p.group;
+        for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM)
+          per_head[c].push_back({g, row0, c, key1 - key0, key0, s, {0, 0}});
+      }
     }
   const size_t per = per_head[0].size();
   if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
     const int xper = pa::NUM_XCD / Hkv;  // XCDs per kv head
     const size_t qlen = (per + xper - 1) / xper;
-    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0});
+    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, {0, 0}});
     for (int x = 0; x < pa::NUM_XCD; ++x) {
       const int c = x / xper, sub = x % xper;
       for (size_t k = 0; k * xper + sub < per; ++k) out[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
@@ -80,7 +101,7 @@ void build_suffix_items(prefix_attn_plan_t& p) {
       const int nrows = p.lens[g] * p.group;
       for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM) {
         const int last_row = std::min(row0 + pa::ROWS_PER_ITEM, nrows) - 1;
-        out.push_back({g, row0, c, last_row / p.group + 1});
+        out.push_back({g, row0, c, last_row / p.group + 1, 0, 0, {0, 0}});
       }
     }
   std::stable_sort(out.begin(), out.end(), [](const WorkItem& a, const WorkItem& b) { return a.nkeys > b.nkeys; });
@@ -204,10 +225,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
   const size_t rows = (size_t)p->T * desc->num_q_heads;
   const size_t o_bytes = align_up(rows * desc->head_dim * sizeof(float), 256);
   const size_t l_bytes = align_up(rows * sizeof(float), 256);
+  const size_t ks = (size_t)p->key_splits;  // the prefix pass leaves one partial per key split
   p->off_o1 = 0;
-  p->off_o2 = o_bytes;
-  p->off_lse1 = 2 * o_bytes;
-  p->off_lse2 = p->off_lse1 + l_bytes;
+  p->off_o2 = ks * o_bytes;
+  p->off_lse1 = (ks + 1) * o_bytes;
+  p->off_lse2 = p->off_lse1 + ks * l_bytes;
   p->off_lse = p->off_lse2 + l_bytes;
   p->off_vtp = p->off_lse + l_bytes;
   size_t end = p->off_vtp;
@@ -294,10 +316,11 @@ int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t
   if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
   const std::vector<WorkItem>& v = plan->items[pass];
   for (size_t n = 0; n < v.size(); ++n) {
-    items_out[4 * n + 0] = v[n].g;
-    items_out[4 * n + 1] = v[n].row0;
-    items_out[4 * n + 2] = v[n].c;
-    items_out[4 * n + 3] = v[n].nkeys;
+    items_out[5 * n + 0] = v[n].g;
+    items_out[5 * n + 1] = v[n].row0;
+    items_out[5 * n + 2] = v[n].c;
+    items_out[5 * n + 3] = v[n].nkeys;
+    items_out[5 * n + 4] = v[n].key0;
   }
   return PA_OK;
 }

@@ -154,11 +154,79 @@ def make_custom(dtype, Hq, Hkv, D, P, suffix_lens, seed=0, name="custom", std=1.
                   vals["v_suffix"], bits)
 
 
-def make_d_out(x: Inputs, seed: int = 1):
+_TENSORS = ("q", "k_prefix", "v_prefix", "k_suffix", "v_suffix")
+
+
+def _rebuild(x: Inputs, w: Workload, lens, pick) -> Inputs:
+    """New Inputs whose tensors are pick(name, x's tensors), applied alike to the values and the bf16 bits."""
+    src = {n: getattr(x, n) for n in _TENSORS}
+    vals = {n: pick(n, src) for n in _TENSORS}
+    bits = {n: pick(n, x.bits) for n in _TENSORS} if x.bits else {}
+    return Inputs(w, np.asarray(lens, dtype=np.int32), vals["q"], vals["k_prefix"], vals["v_prefix"],
+                  vals["k_suffix"], vals["v_suffix"], bits)
+
+
+def share_prompt(x: Inputs) -> Inputs:
+    """The G rollouts of a group answer the same question (Sec. 4.2), so their prompt tokens are the same
+    tokens at the same positions and (the mask being causal) carry the same Q, K and V in every layer:
+    copies rollout 0's prompt rows over the prompt rows of the other rollouts."""
+    Lp = x.workload.prompt_len
+    off = np.concatenate([[0], np.cumsum(x.suffix_lens.astype(np.int64))])
+
+    def pick(name, src):
+        if name.endswith("_prefix"):
+            return src[name]
+        b = src[name].copy()
+        for g in range(1, len(x.suffix_lens)):
+            b[off[g]:off[g] + Lp] = b[:Lp]
+        return b
+    return _rebuild(x, x.workload, x.suffix_lens, pick)
+
+
+def fold_prompt(x: Inputs):
+    """Two-level sharing for inputs whose prompt rows are shared (share_prompt): the prompt joins the prefix.
+    Returns (prompt_call, folded_call, rows):
+      prompt_call   one sequence, prefix = the video tokens, suffix = the prompt (computed once);
+      folded_call   prefix = [video | prompt], suffix of rollout g = its response tokens only;
+      rows          int64 [T]: for packed row t of x, the row of folded_call that holds the same token
+                    (responses), or -(i + 1) for prompt token i (row i of prompt_call).
+    Pure re-arrangement: no arithmetic."""
+    w = x.workload
+    Lp, P = w.prompt_len, w.prefix_len
+    assert Lp > 0 and all(int(s) > Lp for s in x.suffix_lens)
+    off = np.concatenate([[0], np.cumsum(x.suffix_lens.astype(np.int64))])
+    resp = np.concatenate([np.arange(off[g] + Lp, off[g + 1]) for g in range(len(x.suffix_lens))])
+    common = dict(dtype=w.dtype, num_q_heads=w.num_q_heads, num_kv_heads=w.num_kv_heads, head_dim=w.head_dim,
+                  tokens_per_frame=1, seed=w.seed)
+    w_prompt = Workload(w.name + "-prompt", frames=P, prompt_len=Lp, num_rollouts=1, response_len=0, **common)
+    w_folded = Workload(w.name + "-folded", frames=P + Lp, prompt_len=0, num_rollouts=w.num_rollouts,
+                        response_len=None, **common)
+
+    def pick_prompt(name, src):
+        return src[name] if name.endswith("_prefix") else np.ascontiguousarray(src[name][:Lp])
+
+    def pick_folded(name, src):
+        if name.endswith("_prefix"):
+            return np.concatenate([src[name], src[name[0] + "_suffix"][:Lp]])
+        return np.ascontiguousarray(src[name][resp])
+    prompt_call = _rebuild(x, w_prompt, [Lp], pick_prompt)
+    folded_call = _rebuild(x, w_folded, x.suffix_lens - Lp, pick_folded)
+    rows = np.empty(int(off[-1]), dtype=np.int64)
+    rows[resp] = np.arange(len(resp))
+    for g in range(len(x.suffix_lens)):
+        rows[off[g]:off[g] + Lp] = -(np.arange(Lp) + 1)
+    return prompt_call, folded_call, rows
+
+
+def make_d_out(x: Inputs, seed: int = 1, grid: Optional[float] = None):
     """Upstream gradient dL/d(out) for the backward: iid N(0,1) of the shape of q, rounded to bf16 for
-    bf16 workloads.  Returns (fp32 values both sides consume, uint16 bit patterns or None)."""
+    bf16 workloads.  Returns (fp32 values both sides consume, uint16 bit patterns or None).
+    With `grid` (a power of two, e.g. 1/8) the values are first rounded to multiples of it, so that
+    sums of a few of them are still exact in bf16."""
     rng = np.random.default_rng(1000003 * (x.workload.seed + 1) + seed)
     raw = rng.standard_normal(x.q.shape, dtype=np.float32)
+    if grid is not None:
+        raw = (np.rint(raw / np.float32(grid)) * np.float32(grid)).astype(np.float32)
     if x.workload.dtype == "bf16":
         bits, vals = round_to_bf16(raw)
         return vals, bits

@@ -35,6 +35,8 @@ EDGE = [
     ("bf16", 14, 2, 64, 257, (100, 300)),            # head_dim 64
     ("bf16", 7, 1, 128, 1000, (37,) * 5),            # one GQA group, many short rollouts
     ("bf16", 2, 2, 128, 129, (513,)),                # rows cross several work items with group = 1
+    ("bf16", 28, 4, 128, 5000, (40, 3)),             # few rows, long prefix: 9 key ranges, the last one ragged
+    ("bf16", 8, 2, 64, 3000, (17,)),                 # the same with head_dim 64 (5 key ranges)
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),

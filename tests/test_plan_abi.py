@@ -94,24 +94,32 @@ def coverage(plan, Hq, Hkv, P, lens):
     assert bm > 0 and bn > 0
     for which in (0, 1):
         items = plan.items(which)
-        seen = [[np.zeros(S * r, dtype=np.int32) for S in lens] for _ in range(Hkv)]
-        for g, row0, c, nkeys in items:
+        seen = [[np.zeros(S * r, dtype=np.int64) for S in lens] for _ in range(Hkv)]
+        ranges = {}
+        for g, row0, c, nkeys, key0 in items:
             if g < 0:
                 continue
             assert 0 <= g < len(lens) and 0 <= c < Hkv and row0 % bm == 0
             n = lens[g] * r
             assert row0 < n
             hi = min(row0 + bm, n)
-            seen[c][g][row0:hi] += 1
-            if which == 0:
-                assert nkeys == P                        # the whole prefix rectangle, no mask
+            if which == 0:                               # the prefix rectangle, no mask; possibly in key ranges
+                assert key0 % bn == 0 and nkeys > 0
+                ranges.setdefault((c, g, row0), []).append((key0, key0 + nkeys))
             else:
+                seen[c][g][row0:hi] += 1
+                assert key0 == 0
                 last_pos = (hi - 1) // r
                 assert nkeys == last_pos + 1             # keys 0..position of the item's last row
                 assert nkeys <= lens[g]
         if which == 0 and P == 0:
             assert len(items) == 0
             continue
+        if which == 0:                                   # the key ranges of a block of rows tile [0, P)
+            for (c, g, row0), rs in ranges.items():
+                rs.sort()
+                assert rs[0][0] == 0 and rs[-1][1] == P and all(a[1] == b[0] for a, b in zip(rs, rs[1:]))
+                seen[c][g][row0:min(row0 + bm, lens[g] * r)] += 1
         for c in range(Hkv):
             for g in range(len(lens)):
                 assert (seen[c][g] == 1).all(), (which, c, g)
@@ -120,10 +128,27 @@ def coverage(plan, Hq, Hkv, P, lens):
 @pytest.mark.parametrize("Hq,Hkv,P,lens", [
     (28, 4, 4096, [1152] * 8), (28, 4, 100, [1, 37, 300, 5]), (4, 4, 0, [70, 3]), (8, 1, 64, [64]),
     (6, 3, 1000, [257, 256, 255]), (16, 16, 130, [33] * 5),
+    (28, 4, 32768, [256]), (28, 4, 1000, [5, 3]), (8, 2, 70000, [40, 1, 17]),      # few rows: prefix keys are split
 ])
 def test_schedule_covers_every_pair_exactly_once(Hq, Hkv, P, lens):
     plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
     coverage(plan, Hq, Hkv, P, lens)
+
+
+def test_few_rows_split_the_prefix_keys_and_size_the_workspace():
+    """28 blocks of rows for 256 CUs: 9 key ranges per block (one round of workgroups), one fp32 partial each."""
+    Hq, Hkv, D, P, S = 28, 4, 128, 32768, 256
+    plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, prefix_len=P, suffix_lens=[S])
+    items = plan.items(0)
+    real = items[items[:, 0] >= 0]
+    assert len(real) == 28 * 9
+    assert sorted(set(real[:, 4].tolist())) == [i * 57 * 64 for i in range(9)]      # 512 tiles in ranges of 57
+    rows = S * Hq
+    partials = (9 + 1) * rows * D * 4 + (9 + 2) * rows * 4
+    images = Hkv * (P // 64 + S // 64) * D * 64 * 2
+    assert partials + images <= plan.workspace_bytes <= partials + images + 24 * 256
+    f32 = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, prefix_len=P, suffix_lens=[S], dtype="f32")
+    assert len(f32.items(0)) == 28 + 4                                              # fp32 path: no key splits (32 = 8 XCD queues x 4)
 
 
 def test_prefix_items_are_grouped_by_kv_head_per_xcd():
@@ -131,7 +156,7 @@ def test_prefix_items_are_grouped_by_kv_head_per_xcd():
     plan = host_plan()
     items = plan.items(0)
     for x in range(8):
-        heads = {int(c) for g, _, c, _ in items[x::8] if g >= 0}
+        heads = {int(it[2]) for it in items[x::8] if it[0] >= 0}
         assert len(heads) == 1
     # suffix pass is issued longest first
     nk = plan.items(1)[:, 3]
