@@ -227,8 +227,10 @@ def main():
 
 
 def folded_main(args, pa, wl, torch):
-    """Forward with the shared question folded into the prefix (prompt call + folded call per step) next to
-    the one-call form on the same shared-prompt values."""
+    """The shared question folded into the prefix (prompt call + folded call per step) next to the one-call
+    form on the same shared-prompt values; forward, or with --direction backward the gradient pass (whose dO
+    values are arbitrary here: timing only, parity is the tests' job)."""
+    backward = args.direction == "backward"
     w = wl.WORKLOADS[args.workload]
     x = wl.share_prompt(wl.make_inputs(w))
     prompt_call, folded_call, _ = wl.fold_prompt(x)
@@ -242,12 +244,24 @@ def folded_main(args, pa, wl, torch):
         ws = torch.empty(plan.workspace_bytes, dtype=torch.uint8, device="cuda")
         out = torch.empty((c.total_suffix, cw.num_q_heads, cw.head_dim), dtype=torch.bfloat16, device="cuda")
         lse = torch.empty((cw.num_q_heads, c.total_suffix), dtype=torch.float32, device="cuda")
-        return plan, dev, ws, out, lse
-
-    def run(prepared):
-        plan, dev, ws, out, lse = prepared
         pa.prefix_attn_forward(plan, *dev, out, ws)
         pa.prefix_attn_lse(plan, ws, lse)
+        bwd = None
+        if backward:
+            d_out = torch.randn(out.shape, dtype=torch.float32, device="cuda").to(torch.bfloat16)
+            grads = [torch.empty_like(t) for t in dev]
+            bws = torch.empty(plan.backward_workspace_bytes, dtype=torch.uint8, device="cuda")
+            bwd = (d_out, grads, bws)
+        return plan, dev, ws, out, lse, bwd
+
+    def run(prepared):
+        plan, dev, ws, out, lse, bwd = prepared
+        if backward:
+            d_out, grads, bws = bwd
+            pa.prefix_attn_backward(plan, *dev, out, d_out, lse, *grads, bws)
+        else:
+            pa.prefix_attn_forward(plan, *dev, out, ws)
+            pa.prefix_attn_lse(plan, ws, lse)
 
     def timed(calls):
         for _ in range(args.warmup):
@@ -267,12 +281,14 @@ def folded_main(args, pa, wl, torch):
     one_call = [prepare(x)]
     ms_fold = timed(two_level)
     ms_one = timed(one_call)
-    flop_fold = sum(wl.effective_flop(w.num_q_heads, w.head_dim, c.workload.prefix_len, c.suffix_lens)
+    count = wl.backward_flop if backward else wl.effective_flop
+    flop_fold = sum(count(w.num_q_heads, w.head_dim, c.workload.prefix_len, c.suffix_lens)
                     for c in (prompt_call, folded_call))
-    flop_one = wl.effective_flop(w.num_q_heads, w.head_dim, w.prefix_len, x.suffix_lens)
+    flop_one = count(w.num_q_heads, w.head_dim, w.prefix_len, x.suffix_lens)
     tflops = flop_fold / (ms_fold * 1e-3) * 1e-12
     print(json.dumps({
-        "metric": "effective attention TFLOP/s", "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "metric": "effective attention backward TFLOP/s" if backward else "effective attention TFLOP/s",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_fold, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": f"{w.name} with one question shared by all rollouts, prompt folded into the prefix: "

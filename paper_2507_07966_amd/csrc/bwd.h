@@ -44,7 +44,10 @@ struct BwdDqArgs {
   const float* lse2s;     // [Hkv][Mpad] LSE * log2(e) per stacked row (from the pre-pass)
   const float* deltas;    // [Hkv][Mpad] -delta per stacked row
   void* dq;               // [T, Hq, D]
-  const WorkItem* items;  // the suffix pass's list: (g, row0, c, causal extent)
+  float* dq_partial;      // key_splits > 1: fp32 partial dQ [key_splits][T][Hq][D]
+  int32_t key_splits;
+  int64_t T;
+  const WorkItem* items;  // the plan's dQ list: (g, row0, c, causal extent, prefix key range, split)
   const int32_t* cu;
   const int32_t* vt_off;
   int64_t num_items, P, Mpad;

@@ -137,8 +137,11 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
   a.deltas = reinterpret_cast<const float*>(ws + plan->boff_deltas);
   a.Mpad = plan->Mpad;
   a.dq = x.dq;
-  a.items = plan->d_items[1];
-  a.num_items = (int64_t)plan->items[1].size();
+  a.dq_partial = reinterpret_cast<float*>(ws + plan->boff_dqpart);
+  a.key_splits = plan->key_splits;
+  a.T = plan->T;
+  a.items = plan->d_dq_items;
+  a.num_items = (int64_t)plan->dq_items.size();
   a.cu = plan->d_cu;
   a.vt_off = plan->d_vt_off;
   a.P = d.prefix_len;

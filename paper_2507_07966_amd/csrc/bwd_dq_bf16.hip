@@ -24,14 +24,16 @@ using namespace mt;
 constexpr int DQ_WAVES = ROWS_PER_ITEM / 32;
 constexpr int DQ_THREADS = DQ_WAVES * 64;
 
-template <int D>
+// PARTIAL (calls with few rows): the item sweeps only the prefix keys [key0, key0 + pkeys) (split 0:
+// also the own keys) and leaves an unscaled fp32 partial dQ in slot `split`; a reduction adds the slots.
+template <int D, bool PARTIAL>
 __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ d_out, const __bf16* __restrict__ k_prefix,
     const __bf16* __restrict__ v_prefix, const __bf16* __restrict__ k_suffix, const __bf16* __restrict__ v_suffix,
     const __bf16* __restrict__ kt_prefix, const __bf16* __restrict__ kt_suffix, const float* __restrict__ lse2s,
-    const float* __restrict__ deltas, int64_t Mpad, __bf16* __restrict__ dq, const WorkItem* __restrict__ items,
-    const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int P, int tiles_prefix, int tiles_suffix,
-    int Hq, int Hkv, int group, float scale) {
+    const float* __restrict__ deltas, int64_t Mpad, __bf16* __restrict__ dq, float* __restrict__ dq_partial,
+    int64_t part_rows, const WorkItem* __restrict__ items, const int32_t* __restrict__ cu,
+    const int32_t* __restrict__ vt_off, int tiles_prefix, int tiles_suffix, int Hq, int Hkv, int group, float scale) {
   using G = Geo<D>;
   constexpr int KK = G::KK, DB = G::DB;
   constexpr int STAGE = 2 * G::ROW_TILE_BYTES + G::IMAGE_BYTES;  // K tile, V tile, K^T image
@@ -45,7 +47,8 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   const int off_g = cu[it.g];
   const int S_g = cu[it.g + 1] - off_g;
   const int nrows = S_g * group;
-  const int nkeys = it.nkeys;  // causal extent of the item's last row
+  const int nkeys = it.nkeys;  // causal extent of the item's last row (0: this split sweeps prefix keys only)
+  const int P = it.pkeys;      // prefix keys this item sweeps, starting at it.key0 (a multiple of the tile)
   const int64_t row_stride = (int64_t)Hkv * D;
 
   // ---- this lane's query: Q and dO columns, LSE and delta
@@ -91,11 +94,11 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   const int tp = (P + TILE - 1) / TILE;
   const int ts = (nkeys + TILE - 1) / TILE;
   const int ntiles = tp + ts;
-  const __bf16* kpb = k_prefix + (int64_t)it.c * D;
-  const __bf16* vpb = v_prefix + (int64_t)it.c * D;
+  const __bf16* kpb = k_prefix + ((int64_t)it.key0 * Hkv + it.c) * D;
+  const __bf16* vpb = v_prefix + ((int64_t)it.key0 * Hkv + it.c) * D;
   const __bf16* ksb = k_suffix + ((int64_t)off_g * Hkv + it.c) * D;
   const __bf16* vsb = v_suffix + ((int64_t)off_g * Hkv + it.c) * D;
-  const __bf16* ktpb = kt_prefix + (int64_t)it.c * tiles_prefix * (D * TILE);
+  const __bf16* ktpb = kt_prefix + ((int64_t)it.c * tiles_prefix + it.key0 / TILE) * (D * TILE);
   const __bf16* ktsb = kt_suffix + ((int64_t)it.c * tiles_suffix + vt_off[it.g]) * (D * TILE);
 
   // The loads of a tile are issued in three pieces so they can be spread over the MFMA stream.
@@ -215,7 +218,18 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   }
 
   // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's query
-  if (orow >= 0) {
+  if (PARTIAL) {
+    if (orow >= 0) {
+      float* op = dq_partial + ((int64_t)it.split * part_rows + orow) * D + 4 * hf;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          const f32x4 w = {dQ[db][4 * a], dQ[db][4 * a + 1], dQ[db][4 * a + 2], dQ[db][4 * a + 3]};
+          *reinterpret_cast<f32x4*>(op + db * 32 + 8 * a) = w;
+        }
+    }
+  } else if (orow >= 0) {
     __bf16* op = dq + orow * D + 4 * hf;
 #pragma unroll
     for (int db = 0; db < DB; ++db)
@@ -228,6 +242,18 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   }
 }
 
+// dq = scale * (sum of the key splits' fp32 partials), 4 channels per thread, fixed order.
+__global__ __launch_bounds__(256) void bwd_dq_reduce_kernel(const float* __restrict__ partial, __bf16* __restrict__ dq,
+                                                            int64_t n4, int splits, float scale) {
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) acc += *reinterpret_cast<const f32x4*>(partial + ((int64_t)s * n4 + i) * 4);
+    acc *= scale;
+    *reinterpret_cast<bf16x4*>(dq + i * 4) = __builtin_convertvector(acc, bf16x4);
+  }
+}
+
 }  // namespace
 
 int launch_bwd_dq_bf16(const BwdDqArgs& a, void* stream) {
@@ -235,13 +261,26 @@ int launch_bwd_dq_bf16(const BwdDqArgs& a, void* stream) {
   hipStream_t s = static_cast<hipStream_t>(stream);
   auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
   const unsigned grid = (unsigned)a.num_items;
-#define PA_LAUNCH(DD)                                                                                             \
-  bwd_dq_kernel<DD><<<grid, DQ_THREADS, 0, s>>>(b(a.q), b(a.d_out), b(a.k_prefix), b(a.v_prefix), b(a.k_suffix), \
-                                                b(a.v_suffix), b(a.kt_prefix), b(a.kt_suffix), a.lse2s, a.deltas, a.Mpad, \
-                                                static_cast<__bf16*>(a.dq), a.items, a.cu, a.vt_off, (int)a.P,   \
-                                                a.tiles_prefix, a.tiles_suffix, a.Hq, a.Hkv, a.group, a.scale)
-  if (a.D == 128) PA_LAUNCH(128); else PA_LAUNCH(64);
+  const bool part = a.key_splits > 1;
+  const int64_t part_rows = a.T * a.Hq;
+#define PA_LAUNCH(DD, PP)                                                                                          \
+  bwd_dq_kernel<DD, PP><<<grid, DQ_THREADS, 0, s>>>(                                                               \
+      b(a.q), b(a.d_out), b(a.k_prefix), b(a.v_prefix), b(a.k_suffix), b(a.v_suffix), b(a.kt_prefix), b(a.kt_suffix), \
+      a.lse2s, a.deltas, a.Mpad, static_cast<__bf16*>(a.dq), a.dq_partial, part_rows, a.items, a.cu, a.vt_off,     \
+      a.tiles_prefix, a.tiles_suffix, a.Hq, a.Hkv, a.group, a.scale)
+  if (a.D == 128) {
+    if (part) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
+  } else {
+    if (part) PA_LAUNCH(64, true); else PA_LAUNCH(64, false);
+  }
 #undef PA_LAUNCH
+  if (hipGetLastError() != hipSuccess) return 1;
+  if (part) {
+    const int64_t n4 = part_rows * a.D / 4;
+    const int64_t want = (n4 + 255) / 256;
+    bwd_dq_reduce_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>(
+        a.dq_partial, static_cast<__bf16*>(a.dq), n4, a.key_splits, a.scale);
+  }
   return (int)hipGetLastError();
 }
 

@@ -28,7 +28,8 @@ struct WorkItem {
   int32_t nkeys;  // keys swept: the item's share of P in the prefix pass, causal extent in the suffix pass
   int32_t key0;   // prefix pass: first prefix key swept (a multiple of KEYS_PER_TILE); suffix pass: 0
   int32_t split;  // prefix pass: which key split this is (its partial lands in slot `split`); else 0
-  int32_t pad_[2];
+  int32_t pkeys;  // backward dQ list only: prefix keys [key0, key0 + pkeys) swept before the nkeys own keys
+  int32_t pad_;
 };
 
 // Backward tile geometry.  The key-stationary pass (dK/dV) gives a workgroup KEYS_PER_KEY_ITEM
@@ -127,6 +128,9 @@ struct prefix_attn_plan {
   int32_t tiles_prefix = 0, tiles_suffix = 0;
   int32_t key_splits = 1;              // prefix-pass items per block of rows (> 1: few rows, the prefix keys are split)
   pa::WorkItem* d_items[2] = {nullptr, nullptr};
+  // backward dQ pass: the suffix list, each block of rows once per key split (split 0 also sweeps the own keys)
+  std::vector<pa::WorkItem> dq_items;
+  pa::WorkItem* d_dq_items = nullptr;
   // workspace layout, byte offsets
   size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;
   // backward: dK/dV work lists (0 = prefix key blocks, 1 = suffix key blocks) and workspace layout
@@ -135,5 +139,5 @@ struct prefix_attn_plan {
   int64_t Mpad = 0;                    // stacked rows per kv head, rounded up to ROWS_PER_ROW_TILE
   int32_t row_splits = 1;              // items per prefix key block (> 1: fp32 partial gradients are reduced)
   size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_lse2s = 0, boff_deltas = 0,
-         boff_toks = 0, boff_ktp = 0, boff_kts = 0, boff_part = 0, bws_bytes = 0;
+         boff_toks = 0, boff_ktp = 0, boff_kts = 0, boff_part = 0, boff_dqpart = 0, bws_bytes = 0;
 };

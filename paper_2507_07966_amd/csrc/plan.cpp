@@ -64,8 +64,9 @@ void build_prefix_items(prefix_attn_plan_t& p) {
     const int64_t fit = pa::NUM_CU / blocks, by_len = p.tiles_prefix / 8;
     p.key_splits = (int32_t)std::max<int64_t>(1, std::min<int64_t>({fit, by_len, PA_MAX_PARTIALS - 1}));
   }
+  const int tiles_per_split = (p.tiles_prefix + p.key_splits - 1) / p.key_splits;
+  p.key_splits = (p.tiles_prefix + tiles_per_split - 1) / tiles_per_split;  // no empty range
   const int KS = p.key_splits;
-  const int tiles_per_split = (p.tiles_prefix + KS - 1) / KS;
   std::vector<std::vector<WorkItem>> per_head(Hkv);
   for (int c = 0; c < Hkv; ++c)
     for (int s = 0; s < KS; ++s) {
@@ -74,14 +75,14 @@ void build_prefix_items(prefix_attn_plan_t& p) {
       for (int g = 0; g < p.desc.num_rollouts; ++g) {
         const int nrows = p.lens[g] * p.group;
         for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM)
-          per_head[c].push_back({g, row0, c, key1 - key0, key0, s, {0, 0}});
+          per_head[c].push_back({g, row0, c, key1 - key0, key0, s, 0, 0});
       }
     }
   const size_t per = per_head[0].size();
   if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
     const int xper = pa::NUM_XCD / Hkv;  // XCDs per kv head
     const size_t qlen = (per + xper - 1) / xper;
-    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, {0, 0}});
+    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
     for (int x = 0; x < pa::NUM_XCD; ++x) {
       const int c = x / xper, sub = x % xper;
       for (size_t k = 0; k * xper + sub < per; ++k) out[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
@@ -101,10 +102,26 @@ void build_suffix_items(prefix_attn_plan_t& p) {
       const int nrows = p.lens[g] * p.group;
       for (int row0 = 0; row0 < nrows; row0 += pa::ROWS_PER_ITEM) {
         const int last_row = std::min(row0 + pa::ROWS_PER_ITEM, nrows) - 1;
-        out.push_back({g, row0, c, last_row / p.group + 1, 0, 0, {0, 0}});
+        out.push_back({g, row0, c, last_row / p.group + 1, 0, 0, 0, 0});
       }
     }
   std::stable_sort(out.begin(), out.end(), [](const WorkItem& a, const WorkItem& b) { return a.nkeys > b.nkeys; });
+}
+
+// Backward, dQ pass: the suffix pass's blocks of rows (longest first); each sweeps the prefix and
+// then its own keys.  With key splits (few rows, see build_prefix_items) a block appears once per
+// prefix key range; split 0 also sweeps the own keys, and the fp32 partial dQ are added afterwards.
+void build_dq_items(prefix_attn_plan_t& p) {
+  p.dq_items.clear();
+  const int P = (int)p.desc.prefix_len;
+  const int KS = p.key_splits;
+  const int tiles_per_split = (p.tiles_prefix + KS - 1) / KS;  // the ranges of build_prefix_items
+  for (int s = 0; s < KS; ++s) {
+    const int key0 = std::min(s * tiles_per_split * pa::KEYS_PER_TILE, P);
+    const int key1 = std::min((s + 1) * tiles_per_split * pa::KEYS_PER_TILE, P);
+    for (const WorkItem& it : p.items[1])
+      p.dq_items.push_back({it.g, it.row0, it.c, s == 0 ? it.nkeys : 0, key0, s, key1 - key0, 0});
+  }
 }
 
 // Backward, dK/dV pass: one item per block of KEYS_PER_KEY_ITEM keys of a kv head.  A prefix
@@ -120,13 +137,25 @@ void build_key_items(prefix_attn_plan_t& p) {
   pre.clear();
   p.row_splits = 1;
   if (P > 0) {
-    // A short prefix has few key blocks: split the streamed rows so that about two items per CU
-    // exist, each still streaming at least 64 row tiles.
+    // One workgroup per CU runs at a time and all items of a launch take equally long, so the launch
+    // takes ceil(items / CUs) rounds.  Few key blocks (a short prefix) leave CUs idle, and a count
+    // just above a multiple of the CU count pays a whole round for its tail.  Splitting the streamed
+    // rows over R items per key block shortens the rounds; it costs a prologue/epilogue per item
+    // (about 3 tile steps) and, for R > 1, writing and re-reading fp32 partials (about 0.03 tile
+    // steps per item).  Take the R that minimises this estimate; keep R = 1 unless it gains 2 %.
     const int64_t row_tiles = p.Mpad / pa::ROWS_PER_ROW_TILE;
     const int64_t blocks = (int64_t)Hkv * ((P + KB - 1) / KB);
-    int64_t R = (512 + blocks - 1) / blocks;
-    R = std::min<int64_t>(R, std::max<int64_t>(1, row_tiles / 64));
-    R = std::max<int64_t>(1, std::min<int64_t>(R, 16));
+    auto cost = [&](int64_t r) {
+      const int64_t rounds = (blocks * r + pa::NUM_CU - 1) / pa::NUM_CU;
+      return (double)rounds * ((double)((row_tiles + r - 1) / r) + 3.0) + (r > 1 ? 0.03 * (double)(blocks * r) : 0.0);
+    };
+    int64_t R = 1;
+    double best = 0.98 * cost(1);
+    for (int64_t r = 2; r <= 16 && row_tiles / r >= 64; ++r)
+      if (cost(r) < best) {
+        best = cost(r);
+        R = r;
+      }
     p.row_splits = (int32_t)R;
     const int64_t per_split = (row_tiles + R - 1) / R;
     std::vector<std::vector<pa::KeyItem>> per_head(Hkv);
@@ -186,6 +215,8 @@ void layout_backward_workspace(prefix_attn_plan_t& p) {
     p.boff_part = end;  // fp32 partial dK, dV of the prefix per row split: [2][row_splits][P][Hkv][D]
     if (p.row_splits > 1)
       end += align_up((size_t)2 * p.row_splits * d.prefix_len * d.num_kv_heads * d.head_dim * sizeof(float), 256);
+    p.boff_dqpart = end;  // fp32 partial dQ per key split: [key_splits][T][Hq][D]
+    if (p.key_splits > 1) end += align_up((size_t)p.key_splits * rows * d.head_dim * sizeof(float), 256);
   }
   p.bws_bytes = end;
 }
@@ -216,6 +247,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     p->group = desc->num_q_heads / desc->num_kv_heads;
     build_prefix_items(*p);
     build_suffix_items(*p);
+    build_dq_items(*p);
     p->Mpad = ((int64_t)p->T * p->group + pa::ROWS_PER_ROW_TILE - 1) / pa::ROWS_PER_ROW_TILE * pa::ROWS_PER_ROW_TILE;
     build_key_items(*p);
   } catch (const std::bad_alloc&) {
@@ -256,6 +288,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
         ok = hipMalloc((void**)&p->d_items[s], bytes) == hipSuccess &&
              hipMemcpy(p->d_items[s], p->items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
       }
+      if (ok && !p->dq_items.empty()) {
+        const size_t bytes = p->dq_items.size() * sizeof(WorkItem);
+        ok = hipMalloc((void**)&p->d_dq_items, bytes) == hipSuccess &&
+             hipMemcpy(p->d_dq_items, p->dq_items.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+      }
       for (int s = 0; ok && s < 2; ++s) {
         if (p->key_items[s].empty()) continue;
         const size_t bytes = p->key_items[s].size() * sizeof(pa::KeyItem);
@@ -282,6 +319,7 @@ void prefix_attn_destroy(prefix_attn_plan_t* plan) {
     if (plan->d_items[s]) (void)hipFree(plan->d_items[s]);
   for (int s = 0; s < 2; ++s)
     if (plan->d_key_items[s]) (void)hipFree(plan->d_key_items[s]);
+  if (plan->d_dq_items) (void)hipFree(plan->d_dq_items);
   delete plan;
 }
 

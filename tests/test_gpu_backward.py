@@ -35,6 +35,8 @@ EDGE = [
     ("bf16", 2, 2, 128, 129, (513,)),                # group = 1, key blocks with a ragged tail
     ("bf16", 6, 2, 128, 200, (130, 127, 1, 129)),    # rollout boundaries inside row tiles and key blocks
     ("bf16", 8, 2, 64, 300, (1500, 700, 1)),         # short prefix, many rows: prefix key blocks split over row ranges
+    ("bf16", 28, 4, 128, 5000, (40, 3)),             # few rows, long prefix: dQ over 9 prefix key ranges
+    ("bf16", 8, 2, 64, 3000, (17,)),                 # the same with head_dim 64
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),

@@ -147,6 +147,11 @@ def test_few_rows_split_the_prefix_keys_and_size_the_workspace():
     partials = (9 + 1) * rows * D * 4 + (9 + 2) * rows * 4
     images = Hkv * (P // 64 + S // 64) * D * 64 * 2
     assert partials + images <= plan.workspace_bytes <= partials + images + 24 * 256
+    # the backward keeps one fp32 partial dQ per key range on top of its unsplit layout
+    one = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, prefix_len=7 * 64, suffix_lens=[S])   # 7 tiles: no split
+    extra_tiles = Hkv * (P // 64 - 7) * D * 64 * 2
+    grown = plan.backward_workspace_bytes - one.backward_workspace_bytes - extra_tiles
+    assert 9 * rows * D * 4 <= grown <= 9 * rows * D * 4 + 512
     f32 = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, prefix_len=P, suffix_lens=[S], dtype="f32")
     assert len(f32.items(0)) == 28 + 4                                              # fp32 path: no key splits (32 = 8 XCD queues x 4)
 
@@ -218,12 +223,14 @@ def test_backward_workspace_and_argument_checks():
     stacked = 2 * Hkv * mpad * D * 2                       # Q and dO gathered into stacked-row order
     images = Hkv * (P // 64 + 8 * (1152 // 64)) * D * 64 * 2
     splits = len([1 for it in plan.key_items(0) if it[2] == 0 and it[1] == 0])     # items of one key block
-    assert splits == 4                                                              # 128 key blocks -> 512 items
+    assert splits == 2                                                              # 128 key blocks -> 256 items, one round
     partials = 2 * splits * P * Hkv * D * 4
     need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images + partials
     assert need <= plan.backward_workspace_bytes <= need + 12 * 256
     c3 = host_plan(prefix_len=32768, suffix_lens=[2304] * 8)
-    assert len(c3.key_items(0)) == 1024                                             # long prefix: no split
+    assert len(c3.key_items(0)) == 1024                                             # 4 full rounds of 256: no split
+    tail = host_plan(prefix_len=32768 + 256, suffix_lens=[2048] * 8)               # 1032 blocks: 8 would pay a fifth round
+    assert len(tail.key_items(0)) == 1032 * 7
     assert host_plan(dtype="f32").backward_workspace_bytes <= 2 * T * Hq * 4 + 2 * 256
     a = 0x10000
     big = plan.backward_workspace_bytes
