@@ -48,12 +48,17 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load the C-ABI library; raises if it has not been built (python -m paper_2507_07966_amd.build)."""
+    """Load the C-ABI library; raises if it has not been built (python -m paper_2507_07966_amd.build).
+
+    torch is imported first: it carries its own copy of the HIP runtime under the same soname, and the
+    tensors whose device pointers the calls receive live in that runtime.  Loading this library before
+    torch would bring in the system's copy as a second runtime in the process, whose allocations fail."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
         raise FileNotFoundError(f"{_LIB_PATH} is missing: build it with `python -m paper_2507_07966_amd.build`")
+    import torch  # noqa: F401  (see above)
     lib = ctypes.CDLL(_LIB_PATH)
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     lib.prefix_attn_plan.restype = ctypes.c_int

@@ -297,3 +297,17 @@ def test_logprob_calls_check_arguments():
     assert f(a, a, a, 5, 64, 10, 1.0, a, None, a, big - 1, None) == 5
     assert lib.grpo_group_advantages(None, 8, 1, a, None) == 1
     assert lib.grpo_group_advantages(a, 0, 1, a, None) == 2
+
+
+def test_loading_the_library_first_does_not_bring_in_a_second_hip_runtime():
+    """In a fresh process, load the library before anything imports torch: exactly one copy of the HIP
+    runtime may be mapped afterwards (torch carries its own; a second one cannot allocate on the device)."""
+    import subprocess
+    import sys
+    code = ("import paper_2507_07966_amd as pa; pa.load_library(); import torch; "
+            "m = open('/proc/self/maps').read(); "
+            "print(len({l.split()[-1] for l in m.splitlines() if 'libamdhip64' in l}))")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.strip() == "1"
