@@ -16,12 +16,19 @@ import sys
 
 
 def short_name(k: str) -> str:
+    # mangled template arguments: <head_dim, causal> / <head_dim, causal, partial> / <head_dim, partial>
     if "pass_bf16_kernel" in k:
-        return "prefix_pass (bf16 MFMA)" if "Lb0E" in k else "suffix_pass (bf16 MFMA)"
+        return "prefix_pass (bf16 MFMA)" if "ELb0E" in k else "suffix_pass (bf16 MFMA)"
+    if "bwd_dkv_reduce" in k:
+        return "bwd_dkv_prefix: add row splits"
+    if "bwd_dq_reduce" in k:
+        return "bwd_dq: add key splits"
     if "bwd_dkv_kernel" in k:
-        return "bwd_dkv_prefix (bf16 MFMA)" if "Lb0E" in k else "bwd_dkv_suffix (bf16 MFMA)"
+        if "ELb1ELb0E" in k:
+            return "bwd_dkv_suffix (bf16 MFMA)"
+        return "bwd_dkv_prefix (bf16 MFMA)" + (", row splits" if "ELb0ELb1E" in k else "")
     if "bwd_dq_kernel" in k:
-        return "bwd_dq (bf16 MFMA)"
+        return "bwd_dq (bf16 MFMA)" + (", key splits" if "ELb1E" in k else "")
     if "bwd_prep" in k:
         return "bwd_prepass"
     if "bwd_dq_f32" in k or "bwd_dkv_f32" in k or "bwd_delta_f32" in k:
