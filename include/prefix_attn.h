@@ -228,15 +228,20 @@ const char* prefix_attn_status_string(int status);
  * row index inside rollout g is m = i * (Hq/Hkv) + (h % (Hq/Hkv)). */
 int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_item, int32_t* keys_per_tile);
 
-/* Number of work items of a pass (0 = prefix pass, 1 = suffix pass), padding items included. */
+/* Number of work items of a pass (0 = prefix pass, 1 = suffix pass, 2 = the backward's dQ pass),
+ * padding items included. */
 int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass);
 
-/* Copy the work list of a pass into items_out [num_items][5] (HOST) in launch order:
+/* Copy the work list of a pass into items_out [num_items][6] (HOST) in launch order:
  * {rollout g (-1 = padding item), first stacked row inside the rollout, kv head c,
- *  number of keys the item sweeps, first key it sweeps}.  A suffix-pass item sweeps the
- * rollout's keys from 0.  A prefix-pass item sweeps the whole prefix unless the call has so
- * few rows that the prefix is cut into several key ranges per block of rows (bf16 only);
- * the ranges of a block are disjoint, cover the prefix, and their partials are merged. */
+ *  nkeys, key0, pkeys}.
+ * Prefix pass: the item sweeps prefix keys [key0, key0 + nkeys); that is the whole prefix
+ * unless the call has so few rows that the prefix is cut into several key ranges per block
+ * of rows (bf16 only): the ranges of a block are disjoint, cover the prefix, and their
+ * partials are merged.  pkeys = 0.
+ * Suffix pass: the item sweeps the rollout's own keys [0, nkeys); key0 = pkeys = 0.
+ * dQ pass: the item sweeps prefix keys [key0, key0 + pkeys) and then the rollout's own keys
+ * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
 /* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding

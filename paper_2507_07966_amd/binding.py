@@ -136,12 +136,12 @@ class PrefixAttnPlan:
         return a.value, b.value
 
     def items(self, which: int) -> np.ndarray:
-        """Work list of pass 0 (prefix) or 1 (suffix): int32 [n, 5] = (g, row0, c, nkeys, key0)."""
+        """Work list of pass 0 (prefix), 1 (suffix) or 2 (backward dQ): int32 [n, 6] = (g, row0, c, nkeys, key0, pkeys)."""
         lib = load_library()
         n = lib.prefix_attn_plan_num_items(self.handle, which)
         if n < 0:
             raise PrefixAttnError(2, "prefix_attn_plan_num_items")
-        out = np.zeros((n, 5), dtype=np.int32)
+        out = np.zeros((n, 6), dtype=np.int32)
         if n:
             st = lib.prefix_attn_plan_items(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
             if st:

@@ -345,20 +345,21 @@ int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_ite
 }
 
 int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass) {
-  if (!plan || pass < 0 || pass > 1) return -1;
-  return (int64_t)plan->items[pass].size();
+  if (!plan || pass < 0 || pass > 2) return -1;
+  return (int64_t)(pass == 2 ? plan->dq_items : plan->items[pass]).size();
 }
 
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out) {
   if (!plan || !items_out) return PA_ERR_NULL;
-  if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
-  const std::vector<WorkItem>& v = plan->items[pass];
+  if (pass < 0 || pass > 2) return PA_ERR_SHAPE;
+  const std::vector<WorkItem>& v = pass == 2 ? plan->dq_items : plan->items[pass];
   for (size_t n = 0; n < v.size(); ++n) {
-    items_out[5 * n + 0] = v[n].g;
-    items_out[5 * n + 1] = v[n].row0;
-    items_out[5 * n + 2] = v[n].c;
-    items_out[5 * n + 3] = v[n].nkeys;
-    items_out[5 * n + 4] = v[n].key0;
+    items_out[6 * n + 0] = v[n].g;
+    items_out[6 * n + 1] = v[n].row0;
+    items_out[6 * n + 2] = v[n].c;
+    items_out[6 * n + 3] = v[n].nkeys;
+    items_out[6 * n + 4] = v[n].key0;
+    items_out[6 * n + 5] = v[n].pkeys;
   }
   return PA_OK;
 }

@@ -96,7 +96,8 @@ def coverage(plan, Hq, Hkv, P, lens):
         items = plan.items(which)
         seen = [[np.zeros(S * r, dtype=np.int64) for S in lens] for _ in range(Hkv)]
         ranges = {}
-        for g, row0, c, nkeys, key0 in items:
+        for g, row0, c, nkeys, key0, pkeys in items:
+            assert pkeys == 0
             if g < 0:
                 continue
             assert 0 <= g < len(lens) and 0 <= c < Hkv and row0 % bm == 0
@@ -123,6 +124,19 @@ def coverage(plan, Hq, Hkv, P, lens):
         for c in range(Hkv):
             for g in range(len(lens)):
                 assert (seen[c][g] == 1).all(), (which, c, g)
+    # the backward's dQ list: every block of rows of the suffix list, its prefix key ranges tiling [0, P) and
+    # its own keys swept by exactly one of its items
+    blocks = {}
+    for g, row0, c, nkeys, key0, pkeys in plan.items(2):
+        assert g >= 0 and key0 % bn == 0
+        blocks.setdefault((g, row0, c), []).append((key0, key0 + pkeys, nkeys))
+    suffix = {(g, row0, c): nk for g, row0, c, nk, _, _ in plan.items(1)}
+    assert set(blocks) == set(suffix)
+    for key, rs in blocks.items():
+        rs.sort()
+        assert rs[0][0] == 0 and rs[-1][1] == P and all(a[1] == b[0] for a, b in zip(rs, rs[1:]))
+        assert all(b > a for a, b, _ in rs) or P == 0
+        assert sorted(nk for _, _, nk in rs) == [0] * (len(rs) - 1) + [suffix[key]]
 
 
 @pytest.mark.parametrize("Hq,Hkv,P,lens", [
