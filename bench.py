@@ -42,6 +42,32 @@ def measured_traffic(workload: str, kernel: str):
     return None
 
 
+def smi_sample():
+    """Clocks and power as rocm-smi reports them right now (None if the tool is absent or fails)."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showmaxpower", "--json"],
+                           capture_output=True, text=True, timeout=20)
+        card = next(iter(json.loads(r.stdout).values()))
+        return {k.strip(" :"): v.strip("()") for k, v in card.items()}
+    except Exception:
+        return None
+
+
+def gpu_state(torch, step, as_found):
+    """The machine's state, not a tuning knob: clocks as found before the first launch, and sampled again
+    while about half a second of the same steps is queued on the GPU (outside the timed region)."""
+    t0 = time.perf_counter()
+    step()
+    torch.cuda.synchronize()
+    n = max(1, min(2000, int(0.5 / max(time.perf_counter() - t0, 1e-4))))
+    for _ in range(n):
+        step()
+    loaded = smi_sample()
+    torch.cuda.synchronize()
+    return {"as_found_idle": as_found, "under_load": loaded}
+
+
 def calibrate_copy(torch):
     """Plain copy kernels of known size (256 MiB read, 256 MiB written each) for scaling traffic counters."""
     src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
@@ -86,6 +112,7 @@ def main():
         sys.exit(1)
     pa.load_library()   # fails loudly if the HIP library is missing
     torch.cuda.set_device(0)
+    args.smi_as_found = smi_sample()
 
     if args.logprob:
         return logprob_main(args, pa, wl, torch)
@@ -143,6 +170,7 @@ def main():
 
     if args.calibrate_copy:
         calibrate_copy(torch)
+    state = gpu_state(torch, step, args.smi_as_found)
 
     flop = wl.effective_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
@@ -181,6 +209,7 @@ def main():
         "plan_ms": round(plan_ms, 3),
         "kernel_ms": {"v_layout_prepass": round(k_prepass_ms, 4), "prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
         "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1),
+        "rocm_smi": state,
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
                      "traffic": measured_traffic(w.name, dom_name)},
