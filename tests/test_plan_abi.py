@@ -9,6 +9,7 @@ import numpy as np
 import pytest
 
 import paper_2507_07966_amd as pa
+from tests.random_shapes import random_shapes
 from paper_2507_07966_amd import binding
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
@@ -147,6 +148,13 @@ def coverage(plan, Hq, Hkv, P, lens):
 def test_schedule_covers_every_pair_exactly_once(Hq, Hkv, P, lens):
     plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
     coverage(plan, Hq, Hkv, P, lens)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,P,lens", random_shapes())
+def test_schedule_covers_random_shapes(Hq, Hkv, D, P, lens):
+    plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, head_dim=D, prefix_len=P, suffix_lens=list(lens))
+    coverage(plan, Hq, Hkv, P, list(lens))
+    key_coverage(plan, Hq, Hkv, P, list(lens))
 
 
 def test_few_rows_split_the_prefix_keys_and_size_the_workspace():
