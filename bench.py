@@ -43,11 +43,20 @@ def measured_traffic(workload: str, kernel: str):
 
 
 def smi_sample():
-    """Clocks and power as rocm-smi reports them right now (None if the tool is absent or fails)."""
+    """Clocks and power as rocm-smi reports them right now (None if the tool is absent or fails).
+    Not sampled under a profiler: its preloaded library initialises the GPU in every child process, and
+    rocm-smi (a script started through `env`) would then replace a GPU-initialised process with another.
+    The script is started as a direct child of this interpreter for the same reason."""
+    import shutil
     import subprocess
+    if any(k.startswith(("ROCPROF", "ROCP_", "ROCTRACER")) for k in os.environ):
+        return None
+    tool = shutil.which("rocm-smi")
+    if tool is None:
+        return None
     try:
-        r = subprocess.run(["rocm-smi", "--showclocks", "--showpower", "--showmaxpower", "--json"],
-                           capture_output=True, text=True, timeout=20)
+        r = subprocess.run([sys.executable, os.path.realpath(tool), "--showclocks", "--showpower", "--showmaxpower",
+                            "--json"], capture_output=True, text=True, timeout=20)
         card = next(iter(json.loads(r.stdout).values()))
         return {k.strip(" :"): v.strip("()") for k, v in card.items()}
     except Exception:
@@ -57,6 +66,8 @@ def smi_sample():
 def gpu_state(torch, step, as_found):
     """The machine's state, not a tuning knob: clocks as found before the first launch, and sampled again
     while about half a second of the same steps is queued on the GPU (outside the timed region)."""
+    if as_found is None:   # no rocm-smi here, or a profiler is attached: launch nothing extra
+        return None
     t0 = time.perf_counter()
     step()
     torch.cuda.synchronize()
