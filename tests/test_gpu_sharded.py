@@ -49,6 +49,7 @@ CASES = [
     ("bf16", 28, 4, 128, 1000, (300, 77, 129), [0, 1000], 0),               # one shard: partial + merge == forward
     ("bf16", 14, 2, 64, 513, (100, 300), [0, 1, 2, 257, 513], 3),           # tiny shards; suffix on the last shard
     ("bf16", 8, 1, 128, 0, (65, 64), [0, 0], 0),                            # no prefix at all
+    ("bf16", 8, 2, 128, 3000, (20, 9), [0, 1500, 3000], 1),                 # few rows: each shard's keys are split again inside the call
     ("f32", 4, 2, 64, 100, (33, 70), [0, 30, 100], 1),
 ]
 
