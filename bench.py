@@ -219,7 +219,8 @@ def main():
         "wall_ms_per_step": round(wall_ms / args.steps, 4),
         "plan_ms": round(plan_ms, 3),
         "kernel_ms": {"v_layout_prepass": round(k_prepass_ms, 4), "prefix_pass": round(k_prefix_ms, 4), "suffix_pass": round(k_suffix_ms, 4), "merge": round(k_merge_ms, 4)},
-        "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1),
+        # bf16 calls combine the two partials in the suffix pass's epilogue: no merge launch (its slot reads ~0)
+        "merge_hbm_gbs": round(merge_bytes / (k_merge_ms * 1e-3) * 1e-9, 1) if k_merge_ms > 0.01 else None,
         "rocm_smi": state,
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),

@@ -126,9 +126,23 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   a.items = plan->d_items[1];
   a.num_items = (int64_t)plan->items[1].size();
   a.causal = true;
+  // bf16, whole call, unsplit prefix: the suffix pass combines its result with the prefix partial in its
+  // epilogue and writes `out` and the merged LSE itself (no merge launch, no suffix partial in memory)
+  const bool fused = mode == FULL && d.dtype == PA_BF16 && ks == 1;
+  if (fused) {
+    a.epilogue = has_prefix ? 2 : 1;
+    a.o1 = o1;
+    a.lse1 = lse1;
+    a.out_final = out;
+    a.lse_final = lse;
+  }
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 
   if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
+  if (fused) {
+    if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
+    return PA_OK;
+  }
   if (ks > 1) {
     if (merge_splits(true, out, mode == FULL ? d.dtype : (int32_t)PA_F32, mode == FULL ? lse : lse_partial) != 0)
       return PA_ERR_HIP;

@@ -88,12 +88,17 @@ __device__ inline float pair_sum(float x) {
   return a + b;
 }
 
-template <int D, bool CAUSAL>
+// EPI (suffix pass only): 0 = leave an fp32 partial; 1 = the partial is the result (no prefix): write it
+// in bf16 with its LSE; 2 = combine with the prefix partial (o1, lse1) by log-sum-exp and write the result.
+template <int D, bool CAUSAL, int EPI>
 __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
-    float* __restrict__ o_part, float* __restrict__ lse_part, const WorkItem* __restrict__ items,
+    float* __restrict__ o_part, float* __restrict__ lse_part, const float* __restrict__ o1,
+    const float* __restrict__ lse1, __bf16* __restrict__ out_final, float* __restrict__ lse_final,
+    const WorkItem* __restrict__ items,
     const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head,
     int64_t part_rows, int Hq, int Hkv, int group, float scale) {
+  static_assert(EPI == 0 || CAUSAL, "only the suffix pass can finish the call");
   using TL = Tile<D>;
   constexpr int KK = D / 16;  // contraction steps of QK^T
   constexpr int DB = D / 32;  // 32-channel blocks of the output
@@ -379,7 +384,33 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   // ---- epilogue: normalise and write the partial.  Register i of block db is channel
   //      db*32 + 8*(i/4) + 4*hf + i%4 of this lane's query.
   const float l = pair_sum(lsum);
-  if (orow >= 0) {
+  if (EPI != 0) {
+    if (orow >= 0) {
+      float lse_f = mref * scale + __logf(l);
+      float a1 = 0.f, a2 = 1.0f / l;
+      if (EPI == 2) {  // weights of the two partials, as in the merge kernel
+        const float l1 = lse1[orow];
+        const float m = fmaxf(l1, lse_f);  // finite: every row sees at least its own key
+        const float w1 = expf(l1 - m), w2 = expf(lse_f - m);
+        const float tot = w1 + w2;
+        const float inv = 1.0f / tot;
+        a1 = w1 * inv;
+        a2 *= w2 * inv;
+        lse_f = m + logf(tot);
+      }
+      __bf16* op = out_final + orow * D + 4 * hf;
+      const float* p1 = o1 + orow * D + 4 * hf;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int a = 0; a < 4; ++a) {
+          f32x4 w = {O[db][4 * a] * a2, O[db][4 * a + 1] * a2, O[db][4 * a + 2] * a2, O[db][4 * a + 3] * a2};
+          if (EPI == 2) w += a1 * *reinterpret_cast<const f32x4*>(p1 + db * 32 + 8 * a);
+          *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * a) = __builtin_convertvector(w, bf16x4);
+        }
+      if (hf == 0) lse_final[orow] = lse_f;
+    }
+  } else if (orow >= 0) {
     const float inv = 1.0f / l;
     const int64_t prow = (CAUSAL ? 0 : (int64_t)it.split * part_rows) + orow;  // key split s fills partial s
     float* op = o_part + prow * D + 4 * hf;
@@ -403,14 +434,23 @@ int launch_pass_bf16(const PassArgs& a, void* stream) {
   const __bf16* k = static_cast<const __bf16*>(a.k);
   const __bf16* vt = static_cast<const __bf16*>(a.vt);
   const unsigned grid = (unsigned)a.num_items;
-#define PA_LAUNCH(DD, CC)                                                                                         \
-  pass_bf16_kernel<DD, CC><<<grid, NTHREADS, 0, s>>>(q, k, vt, a.o_part, a.lse_part, a.items, a.cu, a.vt_off, \
-                                                     a.vt_tiles_per_head, a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
+  __bf16* outf = static_cast<__bf16*>(a.out_final);
+#define PA_LAUNCH(DD, CC, EE)                                                                                      \
+  pass_bf16_kernel<DD, CC, EE><<<grid, NTHREADS, 0, s>>>(q, k, vt, a.o_part, a.lse_part, a.o1, a.lse1, outf,      \
+                                                         a.lse_final, a.items, a.cu, a.vt_off, a.vt_tiles_per_head, \
+                                                         a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
+#define PA_LAUNCH_D(DD)                                                                                            \
+  if (!a.causal) PA_LAUNCH(DD, false, 0);                                                                          \
+  else if (a.epilogue == 0) PA_LAUNCH(DD, true, 0);                                                                \
+  else if (a.epilogue == 1) PA_LAUNCH(DD, true, 1);                                                                \
+  else PA_LAUNCH(DD, true, 2)
+  if (a.epilogue < 0 || a.epilogue > 2 || (!a.causal && a.epilogue != 0)) return 1;
   if (a.D == 128) {
-    if (a.causal) PA_LAUNCH(128, true); else PA_LAUNCH(128, false);
+    PA_LAUNCH_D(128);
   } else {
-    if (a.causal) PA_LAUNCH(64, true); else PA_LAUNCH(64, false);
+    PA_LAUNCH_D(64);
   }
+#undef PA_LAUNCH_D
 #undef PA_LAUNCH
   return (int)hipGetLastError();
 }

@@ -68,6 +68,14 @@ struct PassArgs {
   int32_t Hq, Hkv, D, group;
   float scale;          // softmax scale
   bool causal;          // false: prefix pass (k/v indexed from 0, no mask); true: suffix pass
+  // bf16 suffix pass only: finish the call in the epilogue instead of leaving a partial for the merge kernel.
+  // 0: fp32 partial into o_part / lse_part; 1: no prefix, the result is final; 2: combine with the prefix
+  // partial (o1, lse1).  1 and 2 write `out_final` (bf16 [T, Hq, D]) and `lse_final` ([T, Hq]).
+  int32_t epilogue;
+  const float* o1;
+  const float* lse1;
+  void* out_final;
+  float* lse_final;
 };
 
 struct MergeArgs {
