@@ -13,10 +13,11 @@
  *       s_j = softmax_scale * <q, k_j>,   LSE = ln sum_j exp(s_j),
  *       out = sum_j exp(s_j - LSE) v_j.
  *
- *   The library computes this as three kernels: a prefix pass (no mask; all rollouts'
+ *   The library computes this in three steps: a prefix pass (no mask; all rollouts'
  *   rows of one kv head stacked against LDS-staged prefix K/V tiles), a causal suffix
- *   pass, and a log-sum-exp merge of the two partial results.  On the bf16 path a small
- *   layout pre-pass first rewrites V into transposed, LDS-ready tile images.
+ *   pass, and a log-sum-exp merge of the two partial results (a kernel of its own on the
+ *   fp32 path; on the bf16 path the suffix pass does it in its epilogue).  On the bf16
+ *   path a small layout pre-pass first rewrites V into transposed, LDS-ready tile images.
  *
  * Conventions
  *   - No C++ types, no exceptions and no printing cross this boundary.  Every call
@@ -96,8 +97,8 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
 /* Measurement variant of prefix_attn_forward: same arguments and result, but each of the
  * launches is bracketed by HIP events on `hip_stream` and the call WAITS for them.
  * kernel_ms (HOST [4]) receives the durations in milliseconds of {V layout pre-pass, prefix
- * pass, suffix pass, merge}; the prefix entry is ~0 when P == 0 and the pre-pass entry is ~0
- * for fp32 plans.  Creates and destroys events, so it is not for stream capture or
+ * pass, suffix pass, merge}; the prefix entry is ~0 when P == 0, the pre-pass entry is ~0
+ * for fp32 plans, and the merge entry is ~0 when the suffix pass merges in its epilogue.  Creates and destroys events, so it is not for stream capture or
  * latency-critical loops. */
 int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                               const void* v_prefix, const void* k_suffix, const void* v_suffix,

@@ -1,5 +1,5 @@
-// prefix_attn_forward / prefix_attn_lse: argument checks on the host, then three launches
-// (prefix pass, suffix pass, merge) on the caller's stream.  Nothing here allocates or
+// prefix_attn_forward / prefix_attn_lse: argument checks on the host, then the launches
+// (prefix pass, suffix pass, and a merge where the suffix pass does not do it) on the caller's stream.  Nothing here allocates or
 // synchronises.
 #include <hip/hip_runtime_api.h>
 
