@@ -137,3 +137,20 @@ def test_c5_backward_ragged_sampled_dq_rows_and_value_identity():
         tol = 16 * np.sqrt(n_keys) * 2.0 ** -9 * el       # as in the C3 test; the sums themselves are of order 500
         print(f"C5 backward kv head {c}: |sum dV - sum dO| max {np.abs(lhs - rhs).max():.3e} (tol {tol:.3e})", flush=True)
         assert np.abs(lhs - rhs).max() <= tol
+
+
+def test_c3_shared_question_folded_into_the_prefix_sampled_rows():
+    """Two-level sharing at the 32K-prefix shape: the prompt-only call (28 blocks of rows: its prefix keys are
+    split into 9 ranges) and the call with prefix 33,024 against the oracle's plain per-rollout definition."""
+    from tests.fold_util import unfold_rows
+    w = wl.WORKLOADS["C3"]
+    x = wl.share_prompt(wl.make_inputs(w))
+    p, f, where = wl.fold_prompt(x)
+    po, pl = run_hip(p)
+    fo, fl = run_hip(f)
+    rows = wl.sample_rows(x.suffix_lens, w.prompt_len, 256, 4, seed=17)
+    ro, rl, _ = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens,
+                                             w.scale, rows=rows)
+    out = unfold_rows(where[rows], fo, po)
+    lse = unfold_rows(where[rows], fl.T, pl.T).T
+    check(out, lse, ro, rl, "C3 two-level")
