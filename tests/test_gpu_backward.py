@@ -37,6 +37,7 @@ EDGE = [
     ("bf16", 8, 2, 64, 300, (1500, 700, 1)),         # short prefix, many rows: prefix key blocks split over row ranges
     ("bf16", 28, 4, 128, 5000, (40, 3)),             # few rows, long prefix: dQ over 9 prefix key ranges
     ("bf16", 8, 2, 64, 3000, (17,)),                 # the same with head_dim 64
+    ("bf16", 7, 1, 128, 8192, (1200,)),              # one kv head: prefix key ranges (forward, dQ) and row ranges (dK/dV) at once
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),
