@@ -187,8 +187,10 @@ def main():
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
     prefix_flop = 4 * w.head_dim * w.num_q_heads * T * P
     suffix_flop = flop - prefix_flop
-    if P:
+    if P and k_prefix_ms > 0.02:
         dom_name, dom_flop, dom_ms = "prefix_pass", prefix_flop, k_prefix_ms
+    elif P:   # short prefix: the plan runs one sweep over [prefix | own keys] (timed in the suffix-pass slot)
+        dom_name, dom_flop, dom_ms = "attention_sweep", flop, k_suffix_ms
     else:
         dom_name, dom_flop, dom_ms = "suffix_pass", suffix_flop, k_suffix_ms
     achieved = dom_flop / (dom_ms * 1e-3) * 1e-12

@@ -229,8 +229,8 @@ const char* prefix_attn_status_string(int status);
  * row index inside rollout g is m = i * (Hq/Hkv) + (h % (Hq/Hkv)). */
 int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_item, int32_t* keys_per_tile);
 
-/* Number of work items of a pass (0 = prefix pass, 1 = suffix pass, 2 = the backward's dQ pass),
- * padding items included. */
+/* Number of work items of a pass (0 = prefix pass, 1 = suffix pass, 2 = the backward's dQ pass,
+ * 3 = the forward's single sweep, empty unless the plan uses it), padding items included. */
 int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass);
 
 /* Copy the work list of a pass into items_out [num_items][6] (HOST) in launch order:
@@ -242,7 +242,10 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
  * partials are merged.  pkeys = 0.
  * Suffix pass: the item sweeps the rollout's own keys [0, nkeys); key0 = pkeys = 0.
  * dQ pass: the item sweeps prefix keys [key0, key0 + pkeys) and then the rollout's own keys
- * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0. */
+ * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0.
+ * Single sweep (whole bf16 calls whose prefix is at most 256 tiles and not cut into key
+ * ranges run as one pass per block of rows instead of prefix pass + suffix pass): like the
+ * dQ pass with key0 = 0 and pkeys = P, laid out over the XCDs like the prefix pass. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
 /* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding

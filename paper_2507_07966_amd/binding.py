@@ -136,7 +136,8 @@ class PrefixAttnPlan:
         return a.value, b.value
 
     def items(self, which: int) -> np.ndarray:
-        """Work list of pass 0 (prefix), 1 (suffix) or 2 (backward dQ): int32 [n, 6] = (g, row0, c, nkeys, key0, pkeys)."""
+        """Work list of pass 0 (prefix), 1 (suffix), 2 (backward dQ) or 3 (forward single sweep, empty unless used):
+        int32 [n, 6] = (g, row0, c, nkeys, key0, pkeys)."""
         lib = load_library()
         n = lib.prefix_attn_plan_num_items(self.handle, which)
         if n < 0:

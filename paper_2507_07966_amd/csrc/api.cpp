@@ -97,7 +97,10 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     if (pa::launch_vt_images(t, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;
-  if (has_prefix) {
+  // bf16, whole call, unsplit short prefix (the plan decides): one sweep over [prefix | own keys] per block of
+  // rows does the work of the prefix pass, the suffix pass and the merge (the sweep list carries both extents)
+  const bool sweep = mode == FULL && !plan->sweep_items.empty();
+  if (has_prefix && !sweep) {
     a.k = k_prefix;
     a.v = v_prefix;
     a.vt = ws + plan->off_vtp;
@@ -130,11 +133,19 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   // epilogue and writes `out` and the merged LSE itself (no merge launch, no suffix partial in memory)
   const bool fused = mode == FULL && d.dtype == PA_BF16 && ks == 1;
   if (fused) {
-    a.epilogue = has_prefix ? 2 : 1;
+    a.epilogue = (has_prefix && !sweep) ? 2 : 1;
     a.o1 = o1;
     a.lse1 = lse1;
     a.out_final = out;
     a.lse_final = lse;
+    if (sweep) {
+      a.sweep_prefix = true;
+      a.k_pre = k_prefix;
+      a.vt_pre = ws + plan->off_vtp;
+      a.vt_pre_tiles_per_head = plan->tiles_prefix;
+      a.items = plan->d_sweep_items;
+      a.num_items = (int64_t)plan->sweep_items.size();
+    }
   }
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 

@@ -90,15 +90,19 @@ __device__ inline float pair_sum(float x) {
 
 // EPI (suffix pass only): 0 = leave an fp32 partial; 1 = the partial is the result (no prefix): write it
 // in bf16 with its LSE; 2 = combine with the prefix partial (o1, lse1) by log-sum-exp and write the result.
-template <int D, bool CAUSAL, int EPI>
+// SWEEP (suffix pass with EPI 1 only): the item first sweeps the prefix keys [0, it.pkeys) (no mask) and then
+// the rollout's own keys, all in one online softmax, so its result is the result of the call.
+template <int D, bool CAUSAL, int EPI, bool SWEEP>
 __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
     float* __restrict__ o_part, float* __restrict__ lse_part, const float* __restrict__ o1,
     const float* __restrict__ lse1, __bf16* __restrict__ out_final, float* __restrict__ lse_final,
     const WorkItem* __restrict__ items,
     const int32_t* __restrict__ cu, const int32_t* __restrict__ vt_off, int64_t vt_tiles_per_head,
+    const __bf16* __restrict__ k_pre, const __bf16* __restrict__ vt_pre, int64_t vt_pre_tiles_per_head,
     int64_t part_rows, int Hq, int Hkv, int group, float scale) {
   static_assert(EPI == 0 || CAUSAL, "only the suffix pass can finish the call");
+  static_assert(!SWEEP || (CAUSAL && EPI == 1), "the sweep over prefix and own keys writes the final result");
   using TL = Tile<D>;
   constexpr int KK = D / 16;  // contraction steps of QK^T
   constexpr int DB = D / 32;  // 32-channel blocks of the output
@@ -115,7 +119,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   const int nkeys = it.nkeys;
   const int64_t row_stride = (int64_t)Hkv * D;
   // prefix pass: the item sweeps prefix keys [key0, key0 + nkeys), key0 a multiple of the tile
-  const __bf16* kbase = k + ((int64_t)(CAUSAL ? off_g : it.key0) * Hkv + it.c) * D;
+  const __bf16* kown = k + ((int64_t)(CAUSAL ? off_g : it.key0) * Hkv + it.c) * D;
   const __bf16* vtbase = vt + ((int64_t)it.c * vt_tiles_per_head + (CAUSAL ? vt_off[it.g] : it.key0 / BN)) * (D * BN);
 
   // ---- this lane's query column
@@ -163,12 +167,20 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     koffs[n] = (unsigned)((row * row_stride + col) * 2);
   }
   const int64_t ktile_bytes = (int64_t)BN * row_stride * 2;  // bytes per tile of K in global memory
-  const int ntiles = (nkeys + BN - 1) / BN;
-  const int full_tiles = nkeys / BN;  // tiles whose 64 keys all exist
+  // SWEEP: tiles [0, tp) are prefix tiles, tiles [tp, ntiles) the rollout's own
+  const int P = SWEEP ? it.pkeys : 0;
+  const int tp = SWEEP ? (P + BN - 1) / BN : 0;
+  const int ntiles = tp + (nkeys + BN - 1) / BN;
+  const __bf16* kpre = SWEEP ? k_pre + (int64_t)it.c * D : nullptr;
+  const __bf16* vtpre = SWEEP ? vt_pre + (int64_t)it.c * vt_pre_tiles_per_head * (D * BN) : nullptr;
 
-  auto issue_k = [&](int tile, auto buf_c) {  // K tile -> K buffer buf
+  auto issue_k = [&](int gtile, auto buf_c) {  // K tile -> K buffer buf
     unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
-    if (tile < full_tiles) {
+    const bool pre = SWEEP && gtile < tp;
+    const int tile = pre ? gtile : gtile - tp;       // tile index inside its key set
+    const int nkeys = pre ? P : it.nkeys;            // keys of that set
+    const __bf16* kbase = pre ? kpre : kown;
+    if (tile < nkeys / BN) {                         // all 64 keys exist
       const char* base = reinterpret_cast<const char*>(kbase) + tile * ktile_bytes;  // uniform: lives in SGPRs
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n)
@@ -187,9 +199,11 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     }
   };
   const unsigned voffs = (unsigned)(((wave * TL::VBLOCKS_PER_WAVE) * 512 + lane * 8) * 2);
-  auto issue_v = [&](int tile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
+  auto issue_v = [&](int gtile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
     unsigned char* dst = smem + VBUF0 + decltype(buf_c)::value * TL::VBYTES;
-    const char* base = reinterpret_cast<const char*>(vtbase) + (int64_t)tile * (D * BN * 2);  // uniform
+    const bool pre = SWEEP && gtile < tp;
+    const char* base = reinterpret_cast<const char*>(pre ? vtpre : vtbase) +
+                       (int64_t)(pre ? gtile : gtile - tp) * (D * BN * 2);  // uniform
 #pragma unroll
     for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n)
       __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(base + voffs + n * 1024),
@@ -215,11 +229,14 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     return *reinterpret_cast<const bf16x8*>(kbuf + kb * 32 * TL::ROWB + koff[kk]);
   };
   // register i of block kb holds key tile*64 + kb*32 + 8*(i/4) + 4*hf + i%4
-  auto mask_scores = [&](f32x16 (&S)[2], int tile) {
-    const int key_tile0 = tile * BN;
-    const bool need_mask = CAUSAL ? (key_tile0 + BN - 1 > wave_first_pos) : (key_tile0 + BN > nkeys);
+  auto mask_scores = [&](f32x16 (&S)[2], int gtile) {
+    const bool pre = SWEEP && gtile < tp;
+    const bool causal = CAUSAL && !pre;
+    const int key_tile0 = (pre ? gtile : gtile - tp) * BN;
+    const int set_keys = pre ? P : nkeys;
+    const bool need_mask = causal ? (key_tile0 + BN - 1 > wave_first_pos) : (key_tile0 + BN > set_keys);
     if (need_mask) {
-      const int limit = CAUSAL ? pos : nkeys - 1;  // last visible key
+      const int limit = causal ? pos : set_keys - 1;  // last visible key
 #pragma unroll
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -435,16 +452,20 @@ int launch_pass_bf16(const PassArgs& a, void* stream) {
   const __bf16* vt = static_cast<const __bf16*>(a.vt);
   const unsigned grid = (unsigned)a.num_items;
   __bf16* outf = static_cast<__bf16*>(a.out_final);
-#define PA_LAUNCH(DD, CC, EE)                                                                                      \
-  pass_bf16_kernel<DD, CC, EE><<<grid, NTHREADS, 0, s>>>(q, k, vt, a.o_part, a.lse_part, a.o1, a.lse1, outf,      \
-                                                         a.lse_final, a.items, a.cu, a.vt_off, a.vt_tiles_per_head, \
-                                                         a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
+  const __bf16* kpre = static_cast<const __bf16*>(a.k_pre);
+  const __bf16* vtpre = static_cast<const __bf16*>(a.vt_pre);
+#define PA_LAUNCH(DD, CC, EE, SS)                                                                                  \
+  pass_bf16_kernel<DD, CC, EE, SS><<<grid, NTHREADS, 0, s>>>(                                                      \
+      q, k, vt, a.o_part, a.lse_part, a.o1, a.lse1, outf, a.lse_final, a.items, a.cu, a.vt_off, a.vt_tiles_per_head, \
+      kpre, vtpre, a.vt_pre_tiles_per_head, a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
 #define PA_LAUNCH_D(DD)                                                                                            \
-  if (!a.causal) PA_LAUNCH(DD, false, 0);                                                                          \
-  else if (a.epilogue == 0) PA_LAUNCH(DD, true, 0);                                                                \
-  else if (a.epilogue == 1) PA_LAUNCH(DD, true, 1);                                                                \
-  else PA_LAUNCH(DD, true, 2)
+  if (!a.causal) PA_LAUNCH(DD, false, 0, false);                                                                   \
+  else if (a.epilogue == 0) PA_LAUNCH(DD, true, 0, false);                                                         \
+  else if (a.epilogue == 1 && a.sweep_prefix) PA_LAUNCH(DD, true, 1, true);                                        \
+  else if (a.epilogue == 1) PA_LAUNCH(DD, true, 1, false);                                                         \
+  else PA_LAUNCH(DD, true, 2, false)
   if (a.epilogue < 0 || a.epilogue > 2 || (!a.causal && a.epilogue != 0)) return 1;
+  if (a.sweep_prefix && (a.epilogue != 1 || !a.k_pre || !a.vt_pre)) return 1;
   if (a.D == 128) {
     PA_LAUNCH_D(128);
   } else {

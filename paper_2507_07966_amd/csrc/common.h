@@ -19,6 +19,9 @@ constexpr int ROWS_PER_ITEM = PA_ROWS_PER_ITEM;
 constexpr int KEYS_PER_TILE = 64;
 constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
 constexpr int NUM_CU = 256;
+// Whole bf16 calls with at most this many prefix tiles run as one sweep over [prefix | own keys] per block of
+// rows; longer prefixes keep the separate prefix and suffix passes, whose leaner tile loop wins there.
+constexpr int SWEEP_MAX_PREFIX_TILES = 256;
 
 // One entry of a pass's work list.  g < 0 marks a padding entry (the workgroup exits).
 struct WorkItem {
@@ -76,6 +79,12 @@ struct PassArgs {
   const float* lse1;
   void* out_final;
   float* lse_final;
+  // bf16 suffix pass with epilogue 1 only: sweep the prefix keys first (items carry pkeys), in the same
+  // online softmax, so the call is one pass over [prefix | own keys] per block of rows.
+  bool sweep_prefix;
+  const void* k_pre;           // [P, Hkv, D]
+  const void* vt_pre;          // prefix V tile images
+  int64_t vt_pre_tiles_per_head;
 };
 
 struct MergeArgs {
@@ -139,6 +148,10 @@ struct prefix_attn_plan {
   // backward dQ pass: the suffix list, each block of rows once per key split (split 0 also sweeps the own keys)
   std::vector<pa::WorkItem> dq_items;
   pa::WorkItem* d_dq_items = nullptr;
+  // forward sweep over [prefix | own keys] (whole bf16 calls with an unsplit prefix): every block of rows once,
+  // interleaved over the XCDs by kv head like the prefix pass, longest first inside a kv head
+  std::vector<pa::WorkItem> sweep_items;
+  pa::WorkItem* d_sweep_items = nullptr;
   // workspace layout, byte offsets
   size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;
   // backward: dK/dV work lists (0 = prefix key blocks, 1 = suffix key blocks) and workspace layout

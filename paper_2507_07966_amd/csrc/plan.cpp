@@ -124,6 +124,30 @@ void build_dq_items(prefix_attn_plan_t& p) {
   }
 }
 
+// Forward sweep (one pass over [prefix | own keys] per block of rows): the prefix dominates, so the blocks are
+// laid out like the prefix pass's (one kv head per subset of XCDs, sharing its K/V tiles in that L2), and
+// inside a kv head longest first.
+void build_sweep_items(prefix_attn_plan_t& p) {
+  p.sweep_items.clear();
+  const int Hkv = p.desc.num_kv_heads;
+  const int P = (int)p.desc.prefix_len;
+  if (P == 0 || p.key_splits != 1 || p.desc.dtype != PA_BF16 || p.tiles_prefix > pa::SWEEP_MAX_PREFIX_TILES) return;
+  std::vector<std::vector<WorkItem>> per_head(Hkv);
+  for (const WorkItem& it : p.items[1]) per_head[it.c].push_back({it.g, it.row0, it.c, it.nkeys, 0, 0, P, 0});  // sorted already
+  const size_t per = per_head[0].size();
+  if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
+    const int xper = pa::NUM_XCD / Hkv;
+    const size_t qlen = (per + xper - 1) / xper;
+    p.sweep_items.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
+    for (int x = 0; x < pa::NUM_XCD; ++x) {
+      const int c = x / xper, sub = x % xper;
+      for (size_t k = 0; k * xper + sub < per; ++k) p.sweep_items[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
+    }
+  } else {
+    for (int c = 0; c < Hkv; ++c) p.sweep_items.insert(p.sweep_items.end(), per_head[c].begin(), per_head[c].end());
+  }
+}
+
 // Backward, dK/dV pass: one item per block of KEYS_PER_KEY_ITEM keys of a kv head.  A prefix
 // block streams the stacked rows of every rollout, all blocks of a kv head in the same order,
 // so (as in the prefix pass) one kv head's blocks are kept on a fixed subset of XCDs and share
@@ -248,6 +272,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     build_prefix_items(*p);
     build_suffix_items(*p);
     build_dq_items(*p);
+    build_sweep_items(*p);
     p->Mpad = ((int64_t)p->T * p->group + pa::ROWS_PER_ROW_TILE - 1) / pa::ROWS_PER_ROW_TILE * pa::ROWS_PER_ROW_TILE;
     build_key_items(*p);
   } catch (const std::bad_alloc&) {
@@ -288,6 +313,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
         ok = hipMalloc((void**)&p->d_items[s], bytes) == hipSuccess &&
              hipMemcpy(p->d_items[s], p->items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
       }
+      if (ok && !p->sweep_items.empty()) {
+        const size_t bytes = p->sweep_items.size() * sizeof(WorkItem);
+        ok = hipMalloc((void**)&p->d_sweep_items, bytes) == hipSuccess &&
+             hipMemcpy(p->d_sweep_items, p->sweep_items.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+      }
       if (ok && !p->dq_items.empty()) {
         const size_t bytes = p->dq_items.size() * sizeof(WorkItem);
         ok = hipMalloc((void**)&p->d_dq_items, bytes) == hipSuccess &&
@@ -320,6 +350,7 @@ void prefix_attn_destroy(prefix_attn_plan_t* plan) {
   for (int s = 0; s < 2; ++s)
     if (plan->d_key_items[s]) (void)hipFree(plan->d_key_items[s]);
   if (plan->d_dq_items) (void)hipFree(plan->d_dq_items);
+  if (plan->d_sweep_items) (void)hipFree(plan->d_sweep_items);
   delete plan;
 }
 
@@ -345,14 +376,14 @@ int prefix_attn_plan_tiles(const prefix_attn_plan_t* plan, int32_t* rows_per_ite
 }
 
 int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass) {
-  if (!plan || pass < 0 || pass > 2) return -1;
-  return (int64_t)(pass == 2 ? plan->dq_items : plan->items[pass]).size();
+  if (!plan || pass < 0 || pass > 3) return -1;
+  return (int64_t)(pass == 3 ? plan->sweep_items : pass == 2 ? plan->dq_items : plan->items[pass]).size();
 }
 
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out) {
   if (!plan || !items_out) return PA_ERR_NULL;
-  if (pass < 0 || pass > 2) return PA_ERR_SHAPE;
-  const std::vector<WorkItem>& v = pass == 2 ? plan->dq_items : plan->items[pass];
+  if (pass < 0 || pass > 3) return PA_ERR_SHAPE;
+  const std::vector<WorkItem>& v = pass == 3 ? plan->sweep_items : pass == 2 ? plan->dq_items : plan->items[pass];
   for (size_t n = 0; n < v.size(); ++n) {
     items_out[6 * n + 0] = v[n].g;
     items_out[6 * n + 1] = v[n].row0;

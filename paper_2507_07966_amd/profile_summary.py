@@ -12,13 +12,22 @@ from __future__ import annotations
 
 import collections
 import csv
+import re
 import sys
 
 
 def short_name(k: str) -> str:
-    # mangled template arguments: <head_dim, causal> / <head_dim, causal, partial> / <head_dim, partial>
+    # mangled template arguments: <head_dim, causal, epilogue, sweep> / <head_dim, causal, partial> / <head_dim, partial>
     if "pass_bf16_kernel" in k:
-        return "prefix_pass (bf16 MFMA)" if "ELb0E" in k else "suffix_pass (bf16 MFMA)"
+        m = re.search(r"pass_bf16_kernelILi\d+ELb(\d)ELi(\d)ELb(\d)E", k)
+        if m is None:
+            return "attention pass (bf16 MFMA)"
+        causal, epi, sweep = (int(v) for v in m.groups())
+        if not causal:
+            return "prefix_pass (bf16 MFMA)"
+        if sweep:
+            return "attention_sweep (bf16 MFMA)"
+        return "suffix_pass (bf16 MFMA)" + ("" if epi == 0 else ", final" if epi == 1 else ", merging")
     if "bwd_dkv_reduce" in k:
         return "bwd_dkv_prefix: add row splits"
     if "bwd_dq_reduce" in k:

@@ -52,6 +52,20 @@ def test_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
     check(out, lse, ro, rl, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
 
 
+def test_long_prefix_takes_the_separate_passes_full_tensor():
+    """A prefix of more than 256 tiles with enough rows to leave it unsplit: prefix pass, then the suffix pass
+    that merges in its epilogue (shorter prefixes run as one sweep); ragged, full tensor."""
+    import paper_2507_07966_amd as pa
+    shape = (4, 4, 64, 16448, (3000, 2500, 2756))
+    plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 0.125, dtype="bf16", device=-1)
+    assert len(plan.items(0)) >= 129 and len(set(plan.items(0)[:, 4].tolist())) == 1        # unsplit prefix keys
+    x = wl.make_custom("bf16", *shape, seed=13)
+    out, lse = run_hip(x)
+    ro, rl, _ = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens,
+                                             x.workload.scale)
+    check(out, lse, ro, rl, "long prefix, separate passes")
+
+
 def test_large_scores_and_late_maximum():
     """Scores with a wide range, and the largest keys at the very end of the prefix, so the
     running reference maximum has to move late and by a lot."""

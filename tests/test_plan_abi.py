@@ -157,6 +157,22 @@ def test_schedule_covers_random_shapes(Hq, Hkv, D, P, lens):
     key_coverage(plan, Hq, Hkv, P, list(lens))
 
 
+def test_single_sweep_list_only_for_short_unsplit_prefixes():
+    """Whole bf16 calls with a prefix of at most 256 tiles run one sweep per block of rows: the list holds every
+    block of the suffix list once, with the whole prefix, one kv head per XCD subset."""
+    plan = host_plan()                                                                  # P = 4,096: 64 tiles
+    sweep, suffix = plan.items(3), plan.items(1)
+    real = sweep[sweep[:, 0] >= 0]
+    assert sorted(map(tuple, real[:, :4].tolist())) == sorted(map(tuple, suffix[:, :4].tolist()))
+    assert (real[:, 4] == 0).all() and (real[:, 5] == 4096).all()
+    for x in range(8):
+        assert len({int(it[2]) for it in sweep[x::8] if it[0] >= 0}) == 1
+    assert len(host_plan(prefix_len=32768, suffix_lens=[2304] * 8).items(3)) == 0       # 512 tiles: separate passes
+    assert len(host_plan(prefix_len=4096, suffix_lens=[256]).items(3)) == 0             # few rows: key ranges instead
+    assert len(host_plan(dtype="f32").items(3)) == 0
+    assert len(host_plan(prefix_len=0).items(3)) == 0
+
+
 def test_few_rows_split_the_prefix_keys_and_size_the_workspace():
     """28 blocks of rows for 256 CUs: 9 key ranges per block (one round of workgroups), one fp32 partial each."""
     Hq, Hkv, D, P, S = 28, 4, 128, 32768, 256
