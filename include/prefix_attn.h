@@ -51,7 +51,8 @@ typedef enum {
   PA_OK = 0,
   PA_ERR_NULL = 1,        /* a required pointer is NULL */
   PA_ERR_SHAPE = 2,       /* a size is out of range or inconsistent */
-  PA_ERR_UNSUPPORTED = 3, /* valid but not implemented (head_dim, dtype) */
+  PA_ERR_UNSUPPORTED = 3, /* valid but not implemented (head_dim, dtype; bf16: a prefix or one rollout
+                             whose K rows, len * Hkv * D * 2 bytes, reach 2 GiB) */
   PA_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned */
   PA_ERR_WORKSPACE = 5,   /* workspace_bytes is smaller than the plan requires */
   PA_ERR_ALLOC = 6,       /* host or device allocation failed in prefix_attn_plan */

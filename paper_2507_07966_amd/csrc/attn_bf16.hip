@@ -173,6 +173,11 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   const int ntiles = tp + (nkeys + BN - 1) / BN;
   const __bf16* kpre = SWEEP ? k_pre + (int64_t)it.c * D : nullptr;
   const __bf16* vtpre = SWEEP ? vt_pre + (int64_t)it.c * vt_pre_tiles_per_head * (D * BN) : nullptr;
+  // Whole tiles are fetched with buffer loads: uniform tile offset in a scalar register plus the lane's
+  // constant 32-bit offset.  Every such access lies inside the arrays (a ragged last K tile takes the
+  // clamped path below), so the descriptors' range (2 GiB) never comes into play.
+  const rsrc_t krs_own = make_rsrc(kown), vrs_own = make_rsrc(vtbase);
+  const rsrc_t krs_pre = make_rsrc(SWEEP ? kpre : kown), vrs_pre = make_rsrc(SWEEP ? vtpre : vtbase);
 
   auto issue_k = [&](int gtile, auto buf_c) {  // K tile -> K buffer buf
     unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
@@ -181,11 +186,12 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const int nkeys = pre ? P : it.nkeys;            // keys of that set
     const __bf16* kbase = pre ? kpre : kown;
     if (tile < nkeys / BN) {                         // all 64 keys exist
-      const char* base = reinterpret_cast<const char*>(kbase) + tile * ktile_bytes;  // uniform: lives in SGPRs
+      const unsigned soff = (unsigned)(tile * ktile_bytes);
 #pragma unroll
-      for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n)
-        __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(base + koffs[n]),
-                                         (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+      for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
+        unsigned char* d = dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024;
+        if (pre) load_chunk_to_lds(krs_pre, d, koffs[n], soff); else load_chunk_to_lds(krs_own, d, koffs[n], soff);
+      }
     } else {  // last, partial tile: rows past the end repeat the last key; their scores are masked
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
@@ -202,12 +208,12 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   auto issue_v = [&](int gtile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
     unsigned char* dst = smem + VBUF0 + decltype(buf_c)::value * TL::VBYTES;
     const bool pre = SWEEP && gtile < tp;
-    const char* base = reinterpret_cast<const char*>(pre ? vtpre : vtbase) +
-                       (int64_t)(pre ? gtile : gtile - tp) * (D * BN * 2);  // uniform
+    const unsigned soff = (unsigned)((pre ? gtile : gtile - tp) * (D * BN * 2));
 #pragma unroll
-    for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n)
-      __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(base + voffs + n * 1024),
-                                       (LDS_PTR(void))(dst + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
+    for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n) {
+      unsigned char* d = dst + (wave * TL::VBLOCKS_PER_WAVE + n) * 1024;
+      if (pre) load_chunk_to_lds(vrs_pre, d, voffs + n * 1024, soff); else load_chunk_to_lds(vrs_own, d, voffs + n * 1024, soff);
+    }
   };
 
   f32x16 O[DB];

@@ -207,6 +207,11 @@ __device__ inline void issue_linear(unsigned char* dst, rsrc_t r, unsigned byte_
 __device__ inline void load_dword_to_lds(rsrc_t r, unsigned char* dst, unsigned lane_byte_offset, unsigned byte_offset) {
   __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))dst, 4, lane_byte_offset, byte_offset, 0, 0);
 }
+// 16 bytes per lane: lane l's chunk lands at dst + 16*l; the source is base + lane_byte_offset + byte_offset
+// (byte_offset uniform: it travels in a scalar register, so no per-lane address arithmetic is needed)
+__device__ inline void load_chunk_to_lds(rsrc_t r, unsigned char* dst, unsigned lane_byte_offset, unsigned byte_offset) {
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))dst, 16, lane_byte_offset, byte_offset, 0, 0);
+}
 #else
 // The host pass of hipcc still parses kernel bodies but has no buffer-resource type: empty stand-ins.
 struct rsrc_t {};
@@ -216,6 +221,7 @@ __device__ inline void issue_full_row_tile(unsigned char*, rsrc_t, unsigned, con
 template <int BYTES, int NW>
 __device__ inline void issue_linear(unsigned char*, rsrc_t, unsigned, int, int) {}
 __device__ inline void load_dword_to_lds(rsrc_t, unsigned char*, unsigned, unsigned) {}
+__device__ inline void load_chunk_to_lds(rsrc_t, unsigned char*, unsigned, unsigned) {}
 #endif
 
 // Pack four fp32 accumulator registers [r0, r0+4) of a 16-register block into the B operand

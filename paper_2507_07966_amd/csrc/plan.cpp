@@ -37,6 +37,12 @@ int validate(const prefix_attn_desc_t* d) {
   if (T * d->num_q_heads > (int64_t)1 << 31) return PA_ERR_SHAPE;
   if (d->dtype != PA_F32 && d->dtype != PA_BF16) return PA_ERR_UNSUPPORTED;
   if (d->head_dim != 64 && d->head_dim != 128) return PA_ERR_UNSUPPORTED;
+  if (d->dtype == PA_BF16) {  // the bf16 kernels address a key set (the prefix, one rollout) with 32-bit byte offsets
+    const int64_t row_bytes = (int64_t)d->num_kv_heads * d->head_dim * 2, limit = (int64_t)1 << 31;
+    if (d->prefix_len * row_bytes >= limit) return PA_ERR_UNSUPPORTED;
+    for (int g = 0; g < d->num_rollouts; ++g)
+      if (d->suffix_lens[g] * row_bytes >= limit) return PA_ERR_UNSUPPORTED;
+  }
   return PA_OK;
 }
 

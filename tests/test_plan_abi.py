@@ -349,3 +349,16 @@ def test_loading_the_library_first_does_not_bring_in_a_second_hip_runtime():
     out = subprocess.run([sys.executable, "-c", code], cwd=root, capture_output=True, text=True, timeout=300)
     assert out.returncode == 0, out.stderr
     assert out.stdout.strip() == "1"
+
+
+def test_bf16_key_sets_of_2_gib_are_unsupported():
+    """The bf16 kernels address the prefix (and each rollout) with 32-bit byte offsets: 2 GiB of K rows is refused
+    at plan time, just below passes; fp32 plans have no such limit."""
+    rows = (1 << 31) // (4 * 128 * 2)                       # 2,097,152 tokens at Hkv = 4, D = 128
+    with pytest.raises(pa.PrefixAttnError) as e:
+        host_plan(prefix_len=rows, suffix_lens=[8])
+    assert e.value.status == 3
+    with pytest.raises(pa.PrefixAttnError) as e:
+        host_plan(prefix_len=64, suffix_lens=[rows])
+    assert e.value.status == 3
+    host_plan(prefix_len=rows - 1, suffix_lens=[8])
