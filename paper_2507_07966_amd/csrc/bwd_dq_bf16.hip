@@ -7,8 +7,7 @@
 // suffix keys accumulate into one dQ and nothing has to be merged.  Per 32-key block:
 //   S^T  = K Q^T                 (A = K tile rows from LDS,      B = Q in registers)
 //   dW^T = V dO^T                (A = V tile rows from LDS,      B = dO in registers)
-//   dS^T = W^T * (dW^T - delta),  W = exp2(c S - LSE log2 e)      (VALU, per lane = per query; the
-//                                                               dW accumulator starts from -delta)
+//   dS^T = W^T * (dW^T - delta),  W = exp2(c S - LSE log2 e)      (VALU, per lane = per query)
 //   dQ^T += K^T dS^T             (A = transposed K image in LDS, B = dS^T packed to bf16)
 // K, V tiles and the K^T image go global -> LDS with direct-to-LDS loads, double buffered, one
 // barrier per 64-key tile.
@@ -84,11 +83,6 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
     }
   }
   const float c_log2 = scale * 1.4426950408889634f;
-  // every score of a lane belongs to the same query, so dW - delta comes for free when the dW accumulator
-  // starts from -delta in all 16 registers
-  f32x16 ndl;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) ndl[i] = -dl;
 
   int koff[KK], ioff[4];
 #pragma unroll
@@ -178,7 +172,7 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
         if (s == 0) {
           const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
           S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Q[s], zero, 0, 0, 0);
-          W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dOb[s], ndl, 0, 0, 0);  // starts from -delta
+          W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dOb[s], zero, 0, 0, 0);
         } else if (s < KK) {
           S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op0[s], Q[s], S, 0, 0, 0);
           W = __builtin_amdgcn_mfma_f32_32x32x16_bf16(op1[s], dOb[s], W, 0, 0, 0);
@@ -199,7 +193,7 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
 #pragma unroll
               for (int e = 0; e < 4; ++e) {
                 const int i = 4 * a + e;
-                ds[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2)) * W[i];
+                ds[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2)) * (W[i] - dl);
               }
               pack4(ds, 4 * a, dSb);
             }
@@ -212,7 +206,7 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
                 const int i = 4 * a + e;
                 float p = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c_log2, -lse2));
                 if (key_tile0 + kb * 32 + 8 * a + 4 * hf + e > limit) p = 0.f;
-                ds[e] = p * W[i];
+                ds[e] = p * (W[i] - dl);
               }
               pack4(ds, 4 * a, dSb);
             }
