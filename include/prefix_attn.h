@@ -243,7 +243,8 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
  * partials are merged.  pkeys = 0.
  * Suffix pass: the item sweeps the rollout's own keys [0, nkeys); key0 = pkeys = 0.
  * dQ pass: the item sweeps prefix keys [key0, key0 + pkeys) and then the rollout's own keys
- * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0.
+ * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0; the list may hold
+ * padding items.
  * Single sweep (whole bf16 calls whose prefix is at most 256 tiles and not cut into key
  * ranges run as one pass per block of rows instead of prefix pass + suffix pass): like the
  * dQ pass with key0 = 0 and pkeys = P, laid out over the XCDs like the prefix pass. */

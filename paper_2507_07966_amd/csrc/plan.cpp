@@ -128,6 +128,21 @@ void build_dq_items(prefix_attn_plan_t& p) {
     for (const WorkItem& it : p.items[1])
       p.dq_items.push_back({it.g, it.row0, it.c, s == 0 ? it.nkeys : 0, key0, s, key1 - key0, 0});
   }
+  // An unsplit prefix: lay the blocks out over the XCDs by kv head like the prefix pass, so that the
+  // workgroups of an XCD walk the same K, V and K^T tiles together (-0.4 % at a 32K prefix, -1.5 % at 230K).
+  const int Hkv = p.desc.num_kv_heads;
+  if (KS == 1 && P > 0 && Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
+    std::vector<std::vector<WorkItem>> per_head(Hkv);
+    for (const WorkItem& it : p.dq_items) per_head[it.c].push_back(it);  // longest first inside a kv head
+    const size_t per = per_head[0].size();
+    const int xper = pa::NUM_XCD / Hkv;
+    const size_t qlen = (per + xper - 1) / xper;
+    p.dq_items.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
+    for (int x = 0; x < pa::NUM_XCD; ++x) {
+      const int c = x / xper, sub = x % xper;
+      for (size_t k = 0; k * xper + sub < per; ++k) p.dq_items[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
+    }
+  }
 }
 
 // Forward sweep (one pass over [prefix | own keys] per block of rows): the prefix dominates, so the blocks are
