@@ -133,7 +133,7 @@ def coverage(plan, Hq, Hkv, P, lens):
             continue
         assert key0 % bn == 0
         blocks.setdefault((g, row0, c), []).append((key0, key0 + pkeys, nkeys))
-    suffix = {(g, row0, c): nk for g, row0, c, nk, _, _ in plan.items(1)}
+    suffix = {(g, row0, c): nk for g, row0, c, nk, _, _ in plan.items(1) if g >= 0}
     assert set(blocks) == set(suffix)
     for key, rs in blocks.items():
         rs.sort()
