@@ -98,8 +98,9 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
 /* Measurement variant of prefix_attn_forward: same arguments and result, but each of the
  * launches is bracketed by HIP events on `hip_stream` and the call WAITS for them.
  * kernel_ms (HOST [4]) receives the durations in milliseconds of {V layout pre-pass, prefix
- * pass, suffix pass, merge}; the prefix entry is ~0 when P == 0, the pre-pass entry is ~0
- * for fp32 plans, and the merge entry is ~0 when the suffix pass merges in its epilogue.  Creates and destroys events, so it is not for stream capture or
+ * pass, suffix pass, merge}; the prefix entry is ~0 when P == 0 or when the plan runs the
+ * single sweep (then timed in the suffix-pass entry), the pre-pass entry is ~0 for fp32
+ * plans, and the merge entry is ~0 when the suffix pass merges in its epilogue.  Creates and destroys events, so it is not for stream capture or
  * latency-critical loops. */
 int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                               const void* v_prefix, const void* k_suffix, const void* v_suffix,
