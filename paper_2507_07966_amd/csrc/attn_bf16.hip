@@ -1,7 +1,10 @@
 // bf16 MFMA attention pass for gfx950: the prefix pass (no mask, shared video K/V) and the
 // causal suffix pass (a rollout's own prompt+response K/V) are two instantiations of one
 // kernel.  Each produces, per stacked query row, a normalised fp32 partial output and the
-// natural-log LSE over the keys it covers; the merge kernel combines the two.
+// natural-log LSE over the keys it covers.  The two partials are combined by log-sum-exp either
+// by the merge kernel or, for whole calls, in the suffix pass's own epilogue (it reads the prefix
+// partial of its rows and writes the final output).  A third mode of the suffix pass sweeps the
+// prefix keys and then the own keys in one online softmax (short prefixes: one launch, no partials).
 //
 // Why the prefix K/V can be shared at all: the video embeddings are gathered once per step
 // and reused by every rollout (paper Sec. 5.1), so all G rollouts of a question attend to
@@ -14,8 +17,10 @@
 //     Each wavefront owns 32 rows; two wavefronts share a SIMD (<= 256 registers each), so one
 //     wavefront's softmax VALU work also overlaps the other's MFMA work.
 //   - K tiles and the pre-transposed V tile images go global -> LDS with direct-to-LDS
-//     16-byte loads (no staging registers), double buffered, one barrier per tile.  The LDS
-//     layouts are XOR-swizzled so every 16-byte operand read is bank-conflict free.
+//     16-byte loads (no staging registers), double buffered, one barrier per tile.  Whole tiles
+//     use buffer addressing (tile offset in a scalar register + a constant per-lane offset), so
+//     the loads need no per-lane address arithmetic.  The LDS layouts are XOR-swizzled so every
+//     16-byte operand read is bank-conflict free.
 //   - Scores are computed transposed, S^T = K Q^T, with v_mfma_f32_32x32x16_bf16: the
 //     accumulator then holds, per lane, 16 keys of ONE query column, so the row maximum is
 //     in-register plus one exchange between lane l and lane l+32, and the probabilities are
@@ -183,9 +188,9 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
     const bool pre = SWEEP && gtile < tp;
     const int tile = pre ? gtile : gtile - tp;       // tile index inside its key set
-    const int nkeys = pre ? P : it.nkeys;            // keys of that set
+    const int set_keys = pre ? P : nkeys;            // keys of that set
     const __bf16* kbase = pre ? kpre : kown;
-    if (tile < nkeys / BN) {                         // all 64 keys exist
+    if (tile < set_keys / BN) {                      // all 64 keys exist
       const unsigned soff = (unsigned)(tile * ktile_bytes);
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
@@ -198,7 +203,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
         const int row = (wave * TL::KBLOCKS_PER_WAVE + n) * ROWS_PER_BLOCK + lane / LANES_PER_ROW;
         const int col = ((lane % LANES_PER_ROW) ^ swizzle_term(row, TL::ROWB)) * 8;
         int key = tile * BN + row;
-        key = key < nkeys ? key : nkeys - 1;
+        key = key < set_keys ? key : set_keys - 1;
         __builtin_amdgcn_global_load_lds((GLB_PTR(const void))(kbase + key * row_stride + col),
                                          (LDS_PTR(void))(dst + (wave * TL::KBLOCKS_PER_WAVE + n) * 1024), 16, 0, 0);
       }
