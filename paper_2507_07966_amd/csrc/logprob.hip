@@ -108,31 +108,46 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
 #pragma unroll
       for (int i = 0; i < 16; ++i) C[a][b][i] = 0.f;
 
-  int ooff[BK / 16];
+  // Per-lane LDS addresses of the operand reads, one set per buffer (the second buffer lies 64 KiB on,
+  // beyond the reach of a read's immediate offset), so the main loop itself holds no address arithmetic.
+  const unsigned char* wop[2][BK / 16];
+  const unsigned char* hop[2][BK / 16];
 #pragma unroll
-  for (int kk = 0; kk < BK / 16; ++kk) ooff[kk] = row_operand_offset<BK>(l32, hf, kk);
+  for (int bufi = 0; bufi < 2; ++bufi)
+#pragma unroll
+    for (int kk = 0; kk < BK / 16; ++kk) {
+      const int off = row_operand_offset<BK>(l32, hf, kk);
+      wop[bufi][kk] = smem + bufi * LP_STAGE + (wv * 64) * 128 + off;
+      hop[bufi][kk] = smem + bufi * LP_STAGE + PANEL_BYTES + (wt * 128) * 128 + off;
+    }
 
   const int nstages = (d + BK - 1) / BK;  // channels past d read as zero (range-checked loads)
-  issue(0, 0);
-  for (int s = 0; s < nstages; ++s) {
-    const int buf = s & 1;
+  auto stage = [&](int s, auto buf_c) {
+    constexpr int BUF = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of stage s has landed
     __syncthreads();                      // everyone's share has; the other buffer is no longer read
-    if (s + 1 < nstages) issue(s + 1, buf ^ 1);
-    const unsigned char* wp = smem + buf * LP_STAGE + (wv * 64) * 128;
-    const unsigned char* hp = smem + buf * LP_STAGE + PANEL_BYTES + (wt * 128) * 128;
+    if (s + 1 < nstages) issue(s + 1, BUF ^ 1);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 wa[2], hb[4];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) wa[a] = lds_operand(wp + a * 32 * 128 + ooff[kk]);
+      for (int a = 0; a < 2; ++a) wa[a] = lds_operand(wop[BUF][kk] + a * 32 * 128);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) hb[b] = lds_operand(hp + b * 32 * 128 + ooff[kk]);
+      for (int b = 0; b < 4; ++b) hb[b] = lds_operand(hop[BUF][kk] + b * 32 * 128);
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int b = 0; b < 4; ++b) C[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[b], C[a][b], 0, 0, 0);
     }
+  };
+  issue(0, 0);
+  {
+    int s = 0;
+    for (; s + 1 < nstages; s += 2) {
+      stage(s, std::integral_constant<int, 0>{});
+      stage(s + 1, std::integral_constant<int, 1>{});
+    }
+    if (s < nstages) stage(s, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue.  Register i of C[a][b]: vocabulary row v0 + wv*64 + a*32 + 8*(i/4) + 4*hf + i%4,
