@@ -151,8 +151,10 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
 #pragma unroll
     for (int piece = 0; piece < 2; ++piece) issue_piece(tile0, 0, piece);
   }
-  for (int tile = tile0; tile < tile1; ++tile) {
-    const int buf = (tile - tile0) & 1;
+  // The tile body exists once per LDS buffer, so that every LDS address in it is the lane's constant offset
+  // plus an immediate (no address arithmetic in the step stream).
+  auto tile_body = [&](int tile, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS loads of this wavefront have landed
     __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
     // the tile after the last one is the last one again: a harmless reload into the idle buffer,
@@ -254,6 +256,14 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         }
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  {
+    int tile = tile0;
+    for (; tile + 1 < tile1; tile += 2) {
+      tile_body(tile, std::integral_constant<int, 0>{});
+      tile_body(tile + 1, std::integral_constant<int, 1>{});
+    }
+    if (tile < tile1) tile_body(tile, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's key
