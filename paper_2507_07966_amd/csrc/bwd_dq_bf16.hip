@@ -134,8 +134,9 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
 
 #pragma unroll
   for (int piece = 0; piece < 3; ++piece) issue_piece(0, 0, piece);
-  for (int u = 0; u < ntiles; ++u) {
-    const int buf = u & 1;
+  // The tile body exists once per LDS buffer: LDS addresses are then lane constants plus immediates.
+  auto tile_body = [&](int u, auto buf_c) {
+    constexpr int buf = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of tile u has landed
     __syncthreads();                      // everyone's share has; buffer buf^1 is no longer read
     // the tile after the last one is the last one again: a harmless reload into the idle buffer
@@ -215,6 +216,14 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
         }
       }
     }
+  };
+  {
+    int u = 0;
+    for (; u + 1 < ntiles; u += 2) {
+      tile_body(u, std::integral_constant<int, 0>{});
+      tile_body(u + 1, std::integral_constant<int, 1>{});
+    }
+    if (u < ntiles) tile_body(u, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's query
