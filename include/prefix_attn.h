@@ -201,8 +201,8 @@ int prefix_attn_backward_timed(const prefix_attn_plan_t* plan, const void* q, co
  * computed without materialising the [num_tokens, vocab] logits.
  *   hidden   [num_tokens, hidden_dim] bf16, DEVICE      (hidden_dim a multiple of 64, else
  *   lm_head  [vocab, hidden_dim]      bf16, DEVICE       PA_ERR_UNSUPPORTED)
- *   targets  [num_tokens] int32, DEVICE; every id must lie in [0, vocab) (not checked: an id
- *            outside leaves that token's logprob unspecified)
+ *   targets  [num_tokens] int32, DEVICE; an id outside [0, vocab) (an ignore index such as -100 on
+ *            a padded slot) gives that token logprob = NaN, its lse is still computed
  *   logit_scale  1 / sampling temperature, finite and > 0
  *   logprob_out [num_tokens] fp32; lse_out [num_tokens] fp32 or NULL
  *   workspace of at least token_logprob_workspace bytes, DEVICE, 16-byte aligned

@@ -14,8 +14,7 @@ from typing import Optional, Sequence
 import numpy as np
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-# PREFIX_ATTN_LIB selects another build of the same library (for A/B measurements)
-_LIB_PATH = os.environ.get("PREFIX_ATTN_LIB") or os.path.join(HERE, "libprefix_attn.so")
+_LIB_PATH = os.path.join(HERE, "libprefix_attn.so")
 _lib = None
 
 PA_F32, PA_BF16 = 0, 1

@@ -22,11 +22,30 @@ DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                 "-mllvm", "-amdgpu-mfma-vgpr-form=1"]
 
 
+# hipcc hands the target-feature flag to its host pass as well, which does not know it and says so once per
+# translation unit.  Only that exact line is dropped from the logs, and only after check_device_flag() has
+# shown that the device pass accepts the flag silently.
+HOST_PASS_NOTE = "'-packed-fp32-ops' is not a recognized feature for this target (ignoring feature)"
+
+
+def check_device_flag(hipcc: str, bdir: str) -> None:
+    """Compile a one-line kernel for the device only: the device pass must take the flags without comment."""
+    src = os.path.join(bdir, "flag_probe.hip")
+    with open(src, "w") as f:
+        f.write("__global__ void flag_probe(float* p) { p[0] = 1.f; }\n")
+    r = subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-x", "hip", *DEVICE_FLAGS, "--cuda-device-only", "-c",
+                        src, "-o", os.path.join(bdir, "flag_probe.o")], stdout=subprocess.PIPE,
+                       stderr=subprocess.STDOUT, text=True)
+    if r.returncode != 0 or "packed-fp32-ops" in r.stdout:
+        raise RuntimeError(f"the device compilation pass does not accept the build's flags:\n{r.stdout}")
+
+
 def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     bdir = os.path.join(HERE, "_build", os.path.basename(out))
     os.makedirs(bdir, exist_ok=True)
+    check_device_flag(hipcc, bdir)
     procs = []
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")
@@ -40,7 +59,7 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     failed = False
     for src, p in procs:
         log, _ = p.communicate()
-        log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l)
+        log = "\n".join(l for l in log.splitlines() if l.strip() != HOST_PASS_NOTE)
         if p.returncode != 0:
             failed = True
             print(f"[build] {src} FAILED\n{log}", file=sys.stderr)

@@ -12,12 +12,12 @@ namespace pa {
 
 // Tile geometry of the two attention passes: one work item = ROWS_PER_ITEM stacked query
 // rows of one (kv head, rollout); keys are swept in LDS tiles of KEYS_PER_TILE.
-#ifndef PA_ROWS_PER_ITEM
-#define PA_ROWS_PER_ITEM 256
-#endif
-constexpr int ROWS_PER_ITEM = PA_ROWS_PER_ITEM;
+constexpr int ROWS_PER_ITEM = 256;
 constexpr int KEYS_PER_TILE = 64;
-constexpr int NUM_XCD = 8;  // MI355X: workgroup n is dispatched to XCD n % 8
+// The layout the work lists are tuned for (MI355X): 256 compute units in 8 XCDs, workgroup n dispatched to
+// XCD n % 8.  A plan for a device that reports another compute-unit count (a partitioned GPU, say) uses that
+// count and does not interleave its lists over XCDs; host-only plans assume this layout.
+constexpr int NUM_XCD = 8;
 constexpr int NUM_CU = 256;
 // Whole bf16 calls with at most this many prefix tiles run as one sweep over [prefix | own keys] per block of
 // rows; longer prefixes keep the separate prefix and suffix passes, whose leaner tile loop wins there.
@@ -138,6 +138,8 @@ struct prefix_attn_plan {
   std::vector<int32_t> vt_off;         // [G+1] tile-image offsets of the rollouts (KEYS_PER_TILE keys per image)
   int64_t T = 0;
   int32_t group = 1;                   // Hq / Hkv
+  int32_t num_cu = pa::NUM_CU;         // compute units the schedule is sized for
+  int32_t num_xcd = pa::NUM_XCD;       // XCDs the lists are interleaved over (1: no interleaving)
   std::vector<pa::WorkItem> items[2];  // 0 = prefix pass, 1 = suffix pass
   // device-side copies (null for a host-only plan)
   int32_t* d_cu = nullptr;             // cu followed by vt_off, one allocation

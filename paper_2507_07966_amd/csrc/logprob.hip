@@ -223,8 +223,9 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
 // 64 tokens; its 4 thread groups each walk every fourth tile with an online combine, then merge.
 __global__ __launch_bounds__(256) void logprob_finalize_kernel(const float2* __restrict__ partials,
                                                                const float* __restrict__ target_logit,
+                                                               const int32_t* __restrict__ targets,
                                                                float* __restrict__ logprob, float* __restrict__ lse_out,
-                                                               int64_t N, int nparts) {
+                                                               int64_t N, int nparts, int V) {
   __shared__ float2 sm[4][64];
   const int tl = threadIdx.x & 63, grp = threadIdx.x >> 6;
   const int64_t tok = (int64_t)blockIdx.x * 64 + tl;
@@ -249,7 +250,9 @@ __global__ __launch_bounds__(256) void logprob_finalize_kernel(const float2* __r
       ll += v.y > 0.f ? v.y * expf(v.x - mm) : 0.f;  // a group that saw no tile holds (-inf, 0)
     }
     const float lse = mm + logf(ll);
-    logprob[tok] = target_logit[tok] - lse;
+    // no tile holds the logit of an id outside [0, V) (an ignore index, say): its slot was never written
+    const int32_t y = targets[tok];
+    logprob[tok] = (y >= 0 && y < V) ? target_logit[tok] - lse : __builtin_nanf("");
     if (lse_out) lse_out[tok] = lse;
   }
 }
@@ -287,7 +290,7 @@ int launch_logprob(const LogprobArgs& a, void* stream) {
       reinterpret_cast<float2*>(a.partials), a.target_logit, a.N, a.d, a.V, TM, TV, by_tm, a.logit_scale);
   if (hipGetLastError() != hipSuccess) return 1;
   logprob_finalize_kernel<<<(unsigned)((a.N + 63) / 64), 256, 0, s>>>(
-      reinterpret_cast<const float2*>(a.partials), a.target_logit, a.logprob, a.lse, a.N, TV);
+      reinterpret_cast<const float2*>(a.partials), a.target_logit, a.targets, a.logprob, a.lse, a.N, TV, a.V);
   return (int)hipGetLastError();
 }
 

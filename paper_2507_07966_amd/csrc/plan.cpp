@@ -46,6 +46,32 @@ int validate(const prefix_attn_desc_t* d) {
   return PA_OK;
 }
 
+// Lays per-kv-head lists out so that workgroup n (dispatched to XCD n % num_xcd) always belongs to the same
+// kv head: each head owns num_xcd / Hkv XCDs, whose L2 then serves that head's tiles to all the workgroups
+// walking them together.  Slots without an item hold `pad` (the workgroup exits).  When the XCD count is not
+// a multiple of the head count the lists are simply concatenated.
+template <class Item>
+void interleave_over_xcds(const std::vector<std::vector<Item>>& per_head, int num_xcd, const Item& pad,
+                          std::vector<Item>& out) {
+  const int Hkv = (int)per_head.size();
+  out.clear();
+  if (Hkv <= num_xcd && num_xcd % Hkv == 0) {
+    size_t per = 0;
+    for (const auto& v : per_head) per = std::max(per, v.size());
+    const int xper = num_xcd / Hkv;  // XCDs per kv head
+    const size_t qlen = (per + xper - 1) / xper;
+    out.assign(qlen * num_xcd, pad);
+    for (int x = 0; x < num_xcd; ++x) {
+      const int c = x / xper, sub = x % xper;
+      for (size_t k = 0; k * xper + sub < per_head[c].size(); ++k) out[k * num_xcd + x] = per_head[c][k * xper + sub];
+    }
+  } else {
+    for (const auto& v : per_head) out.insert(out.end(), v.begin(), v.end());
+  }
+}
+
+const WorkItem PAD_ITEM{-1, 0, 0, 0, 0, 0, 0, 0};
+
 // Prefix pass: every (kv head, rollout, block of stacked rows) sweeps all P keys.  Workgroup n
 // runs on XCD n % 8 and each XCD has a private L2, so the list is interleaved such that one kv
 // head's items land on a fixed subset of XCDs and walk the prefix K/V tiles together: the
@@ -67,7 +93,7 @@ void build_prefix_items(prefix_attn_plan_t& p) {
     blocks += ((int64_t)p.lens[g] * p.group + pa::ROWS_PER_ITEM - 1) / pa::ROWS_PER_ITEM;
   blocks *= Hkv;
   if (p.desc.dtype == PA_BF16) {  // one round of workgroups, at least 8 tiles per range
-    const int64_t fit = pa::NUM_CU / blocks, by_len = p.tiles_prefix / 8;
+    const int64_t fit = p.num_cu / blocks, by_len = p.tiles_prefix / 8;
     p.key_splits = (int32_t)std::max<int64_t>(1, std::min<int64_t>({fit, by_len, PA_MAX_PARTIALS - 1}));
   }
   const int tiles_per_split = (p.tiles_prefix + p.key_splits - 1) / p.key_splits;
@@ -84,18 +110,7 @@ void build_prefix_items(prefix_attn_plan_t& p) {
           per_head[c].push_back({g, row0, c, key1 - key0, key0, s, 0, 0});
       }
     }
-  const size_t per = per_head[0].size();
-  if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
-    const int xper = pa::NUM_XCD / Hkv;  // XCDs per kv head
-    const size_t qlen = (per + xper - 1) / xper;
-    out.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
-    for (int x = 0; x < pa::NUM_XCD; ++x) {
-      const int c = x / xper, sub = x % xper;
-      for (size_t k = 0; k * xper + sub < per; ++k) out[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
-    }
-  } else {
-    for (int c = 0; c < Hkv; ++c) out.insert(out.end(), per_head[c].begin(), per_head[c].end());
-  }
+  interleave_over_xcds(per_head, p.num_xcd, PAD_ITEM, out);
 }
 
 // Suffix pass: a block of stacked rows needs the rollout's keys 0..(position of its last row).
@@ -131,17 +146,10 @@ void build_dq_items(prefix_attn_plan_t& p) {
   // An unsplit prefix: lay the blocks out over the XCDs by kv head like the prefix pass, so that the
   // workgroups of an XCD walk the same K, V and K^T tiles together (-0.4 % at a 32K prefix, -1.5 % at 230K).
   const int Hkv = p.desc.num_kv_heads;
-  if (KS == 1 && P > 0 && Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
+  if (KS == 1 && P > 0 && Hkv <= p.num_xcd && p.num_xcd % Hkv == 0) {
     std::vector<std::vector<WorkItem>> per_head(Hkv);
     for (const WorkItem& it : p.dq_items) per_head[it.c].push_back(it);  // longest first inside a kv head
-    const size_t per = per_head[0].size();
-    const int xper = pa::NUM_XCD / Hkv;
-    const size_t qlen = (per + xper - 1) / xper;
-    p.dq_items.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
-    for (int x = 0; x < pa::NUM_XCD; ++x) {
-      const int c = x / xper, sub = x % xper;
-      for (size_t k = 0; k * xper + sub < per; ++k) p.dq_items[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
-    }
+    interleave_over_xcds(per_head, p.num_xcd, PAD_ITEM, p.dq_items);
   }
 }
 
@@ -155,18 +163,7 @@ void build_sweep_items(prefix_attn_plan_t& p) {
   if (P == 0 || p.key_splits != 1 || p.desc.dtype != PA_BF16 || p.tiles_prefix > pa::SWEEP_MAX_PREFIX_TILES) return;
   std::vector<std::vector<WorkItem>> per_head(Hkv);
   for (const WorkItem& it : p.items[1]) per_head[it.c].push_back({it.g, it.row0, it.c, it.nkeys, 0, 0, P, 0});  // sorted already
-  const size_t per = per_head[0].size();
-  if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
-    const int xper = pa::NUM_XCD / Hkv;
-    const size_t qlen = (per + xper - 1) / xper;
-    p.sweep_items.assign(qlen * pa::NUM_XCD, WorkItem{-1, 0, 0, 0, 0, 0, 0, 0});
-    for (int x = 0; x < pa::NUM_XCD; ++x) {
-      const int c = x / xper, sub = x % xper;
-      for (size_t k = 0; k * xper + sub < per; ++k) p.sweep_items[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
-    }
-  } else {
-    for (int c = 0; c < Hkv; ++c) p.sweep_items.insert(p.sweep_items.end(), per_head[c].begin(), per_head[c].end());
-  }
+  interleave_over_xcds(per_head, p.num_xcd, PAD_ITEM, p.sweep_items);
 }
 
 // Backward, dK/dV pass: one item per block of KEYS_PER_KEY_ITEM keys of a kv head.  A prefix
@@ -191,7 +188,7 @@ void build_key_items(prefix_attn_plan_t& p) {
     const int64_t row_tiles = p.Mpad / pa::ROWS_PER_ROW_TILE;
     const int64_t blocks = (int64_t)Hkv * ((P + KB - 1) / KB);
     auto cost = [&](int64_t r) {
-      const int64_t rounds = (blocks * r + pa::NUM_CU - 1) / pa::NUM_CU;
+      const int64_t rounds = (blocks * r + p.num_cu - 1) / p.num_cu;
       return (double)rounds * ((double)((row_tiles + r - 1) / r) + 3.0) + (r > 1 ? 0.03 * (double)(blocks * r) : 0.0);
     };
     int64_t R = 1;
@@ -211,18 +208,7 @@ void build_key_items(prefix_attn_plan_t& p) {
           const int32_t t1 = (int32_t)std::min<int64_t>((r + 1) * per_split, row_tiles);
           per_head[c].push_back({-1, key0, c, std::min(KB, P - key0), t0, t1, r, 0});
         }
-    const size_t per = per_head[0].size();
-    if (Hkv <= pa::NUM_XCD && pa::NUM_XCD % Hkv == 0) {
-      const int xper = pa::NUM_XCD / Hkv;
-      const size_t qlen = (per + xper - 1) / xper;
-      pre.assign(qlen * pa::NUM_XCD, pa::KeyItem{-1, 0, -1, 0, 0, 0, 0, 0});
-      for (int x = 0; x < pa::NUM_XCD; ++x) {
-        const int c = x / xper, sub = x % xper;
-        for (size_t k = 0; k * xper + sub < per; ++k) pre[k * pa::NUM_XCD + x] = per_head[c][k * xper + sub];
-      }
-    } else {
-      for (int c = 0; c < Hkv; ++c) pre.insert(pre.end(), per_head[c].begin(), per_head[c].end());
-    }
+    interleave_over_xcds(per_head, p.num_xcd, pa::KeyItem{-1, 0, -1, 0, 0, 0, 0, 0}, pre);
   }
   std::vector<pa::KeyItem>& suf = p.key_items[1];
   suf.clear();
@@ -277,6 +263,18 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
   if (st != PA_OK) return st;
   prefix_attn_plan_t* p = new (std::nothrow) prefix_attn_plan_t();
   if (!p) return PA_ERR_ALLOC;
+  if (desc->device >= 0) {  // size the schedule for the device it will run on
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, desc->device) != hipSuccess || cus < 1) {
+      (void)hipGetLastError();
+      delete p;
+      return PA_ERR_HIP;
+    }
+    if (cus != pa::NUM_CU) {  // not the layout the XCD interleaving is built for
+      p->num_cu = cus;
+      p->num_xcd = 1;
+    }
+  }
   try {
     p->desc = *desc;
     p->lens.assign(desc->suffix_lens, desc->suffix_lens + desc->num_rollouts);

@@ -304,18 +304,33 @@ def algorithmic_bytes(w: Workload, suffix_lens) -> int:
     return qo + kv + 4 * w.num_q_heads * T
 
 
-def sample_rows(suffix_lens, prompt_len: int, tile: int, n_random: int, seed: int = 0) -> np.ndarray:
+def sample_rows(suffix_lens, prompt_len: int, tile: int, n_random: int, seed: int = 0, group: int = 0,
+                rows_per_item: int = 256, item_bounds: Optional[int] = None) -> np.ndarray:
     """Packed token rows for sampled parity: per rollout the first and last row, the rows on
-    both sides of the prompt/response boundary and of every multiple of `tile`, plus random rows."""
+    both sides of the prompt/response boundary and of every multiple of `tile`, plus random rows.
+
+    With `group` (= Hq / Hkv) also the positions around work-item boundaries: a work item covers
+    `rows_per_item` stacked rows m = position * group + head-in-group, so item k starts inside position
+    floor(k * rows_per_item / group); that position (whose heads may be split over two items) and its two
+    neighbours are added, for every boundary of a rollout or, with `item_bounds` = n, for its first, its last
+    and n seeded others."""
     rng = np.random.default_rng(seed + 12345)
     off = np.concatenate([[0], np.cumsum(np.asarray(suffix_lens, dtype=np.int64))])
     rows = []
     for g, S in enumerate(np.asarray(suffix_lens, dtype=np.int64)):
-        local = {0, int(S) - 1}
+        S = int(S)
+        local = {0, S - 1}
         if 0 < prompt_len < S:
             local.update({prompt_len - 1, prompt_len})
-        for b in range(tile, int(S), tile):
+        for b in range(tile, S, tile):
             local.update({b - 1, b})
         local.update(int(x) for x in rng.integers(0, S, size=n_random))
+        if group > 0:
+            ks = np.arange(1, (S * group + rows_per_item - 1) // rows_per_item)
+            if item_bounds is not None and len(ks) > item_bounds + 2:
+                ks = np.concatenate([ks[:1], ks[-1:], rng.choice(ks[1:-1], size=item_bounds, replace=False)])
+            for k in ks:
+                p = int(k) * rows_per_item // group
+                local.update(i for i in (p - 1, p, p + 1) if 0 <= i < S)
         rows.extend(int(off[g]) + i for i in sorted(local))
     return np.asarray(rows, dtype=np.int64)

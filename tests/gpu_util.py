@@ -102,20 +102,28 @@ def run_hip_backward(x, d_out, d_out_bits=None, scale=None, keep=False):
     return res
 
 
+def check_grad_tensor(a, r, dtype, label=""):
+    """One gradient tensor `a` against the oracle's `r` (same shape, last axis = head_dim).  Returns the worst
+    element error in units of the tensor's rms."""
+    assert a.shape == r.shape, f"{label}: shape {a.shape} vs {r.shape}"
+    if r.size == 0:
+        return 0.0
+    assert np.isfinite(a).all(), f"{label}: non-finite gradient"
+    rms = float(np.sqrt(np.mean(r * r)))
+    d = np.abs(a - r)
+    row = np.sqrt(np.mean(r * r, axis=-1, keepdims=True))        # rms of each (token, head) vector
+    excess = np.maximum(d - GRAD_REL[dtype] * np.abs(r), 0.0)
+    in_row_units = float((excess / np.maximum(row, 1e-3 * rms + 1e-300)).max())
+    beyond = float(np.maximum(excess - 2.0 ** -5 * row, 0.0).max() / max(rms, 1e-300))
+    msg = (f"{label}: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (reference rms {rms:.3e}); worst element "
+           f"{d.max() / max(rms, 1e-300):.3e} of the tensor's rms, {in_row_units:.3e} of its vector's rms, "
+           f"beyond {beyond:.3e}")
+    print(msg, flush=True)
+    assert (d <= GRAD_REL[dtype] * np.abs(r) + GRAD_ABS_RMS[dtype] * rms + 1e-30).all(), msg
+    assert d.mean() <= GRAD_MEAN_RMS[dtype] * rms + 1e-30, msg
+    return d.max() / max(rms, 1e-30)
+
+
 def check_grads(got, ref, dtype, label=""):
     """got: dict from run_hip_backward; ref: the oracle's five arrays in GRAD_NAMES order."""
-    worst = 0.0
-    for n, r in zip(GRAD_NAMES, ref):
-        a = got[n]
-        assert a.shape == r.shape, f"{label} {n}: shape {a.shape} vs {r.shape}"
-        if r.size == 0:
-            continue
-        assert np.isfinite(a).all(), f"{label} {n}: non-finite gradient"
-        rms = float(np.sqrt(np.mean(r * r)))
-        d = np.abs(a - r)
-        msg = f"{label} {n}: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (reference rms {rms:.3e})"
-        print(msg, flush=True)
-        assert (d <= GRAD_REL[dtype] * np.abs(r) + GRAD_ABS_RMS[dtype] * rms + 1e-30).all(), msg
-        assert d.mean() <= GRAD_MEAN_RMS[dtype] * rms + 1e-30, msg
-        worst = max(worst, d.max() / max(rms, 1e-30))
-    return worst
+    return max(check_grad_tensor(got[n], r, dtype, f"{label} {n}") for n, r in zip(GRAD_NAMES, ref))

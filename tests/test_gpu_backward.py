@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 
 from oracle import cref
+from oracle import ref_attention as ref
 from paper_2507_07966_amd import workloads as wl
 from tests.gpu_util import GRAD_NAMES, check_grads, run_hip_backward
 
@@ -38,6 +39,7 @@ EDGE = [
     ("bf16", 28, 4, 128, 5000, (40, 3)),             # few rows, long prefix: dQ over 9 prefix key ranges
     ("bf16", 8, 2, 64, 3000, (17,)),                 # the same with head_dim 64
     ("bf16", 7, 1, 128, 8192, (1200,)),              # one kv head: prefix key ranges (forward, dQ) and row ranges (dK/dV) at once
+    ("bf16", 6, 3, 128, 300, (100, 57)),             # 3 kv heads do not divide the 8 XCDs: lists are not interleaved
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),
@@ -51,6 +53,12 @@ def test_backward_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
     print(f"backward edge case {dtype} Hq={Hq} Hkv={Hkv} D={D} P={P} lens={lens}", flush=True)
     got = run_hip_backward(x, do, bits)
     check_grads(got, oracle_backward(x, do), dtype, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
+    # also against the plain definition (numpy: chain rule on the forward formula, softmax Jacobian written out),
+    # which has none of the two-phase structure that the C version shares with the kernels
+    if Hq * sum(lens) * (P + max(lens)) <= 3e7:
+        plain = ref.prefix_shared_attention_backward(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
+                                                     x.suffix_lens, x.workload.scale, do)
+        check_grads(got, plain, dtype, f"edge vs the plain definition {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,P,lens", [(28, 4, 128, 500, (300, 129)), (8, 2, 64, 300, (1500, 700, 1))])
@@ -68,6 +76,24 @@ def test_c2_backward_full_tensor():
     do, bits = wl.make_d_out(x)
     got = run_hip_backward(x, do, bits)
     check_grads(got, oracle_backward(x, do), "bf16", "C2")
+
+
+def test_backward_direct_key_block_path_full_tensor():
+    """Element by element on the dK/dV path the long-prefix configurations take: head_dim 128, 7 query heads per
+    kv head, 512 prefix key blocks (two rounds of workgroups, the last block of a head ragged), every block one
+    work item that streams ALL stacked rows (no row ranges, no partial gradients), ragged rollouts."""
+    import paper_2507_07966_amd as pa
+    shape = (28, 4, 128, 16350, (500, 333, 129, 467, 71))
+    plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 128 ** -0.5, dtype="bf16", device=-1)
+    ki = plan.key_items(0)
+    ki = ki[ki[:, 2] >= 0]
+    row_tiles = (sum(shape[4]) * 7 + 63) // 64
+    assert len(ki) == 4 * 128 and (ki[:, 4] == 0).all() and (ki[:, 5] == row_tiles).all()    # direct path
+    plan.destroy()
+    x = wl.make_custom("bf16", *shape, seed=19)
+    do, bits = wl.make_d_out(x)
+    got = run_hip_backward(x, do, bits)
+    check_grads(got, oracle_backward(x, do), "bf16", "direct dK/dV path, 16K prefix")
 
 
 def test_backward_and_logprob_on_side_stream_and_graph_replay():

@@ -12,7 +12,7 @@ pytestmark = pytest.mark.gpu
 TOL = 1e-3
 
 
-def run_hip(hidden_bits, head_bits, targets, scale=1.0, want_lse=True):
+def run_hip(hidden_bits, head_bits, targets, scale=1.0, want_lse=True, junk_workspace=False):
     import torch
     import paper_2507_07966_amd as pa
     h = torch.from_numpy(hidden_bits.view(np.int16)).cuda().view(torch.bfloat16)
@@ -20,6 +20,8 @@ def run_hip(hidden_bits, head_bits, targets, scale=1.0, want_lse=True):
     y = torch.from_numpy(np.ascontiguousarray(targets, dtype=np.int32)).cuda()
     N, d, V = h.shape[0], h.shape[1], w.shape[0]
     ws = torch.empty(pa.token_logprob_workspace(N, d, V), dtype=torch.uint8, device="cuda")
+    if junk_workspace:      # finite, plausible-looking floats (0.5 ... 2) in every word
+        ws.view(torch.int32).random_(0x3F000000, 0x40000000)
     lp = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full((N,), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
     pa.token_logprob_forward(h, w, y, scale, lp, lse, ws)
@@ -59,6 +61,20 @@ def test_logprob_peaked_and_wide_logits():
     lp, lse = run_hip(x.bits["hidden"], x.bits["lm_head"], x.targets, 1.0)
     rp, rl = ref.token_logprobs(x.hidden, x.lm_head, x.targets, 1.0)
     assert np.abs(lp - rp).max() <= TOL and np.abs(lse - rl).max() <= TOL
+
+
+def test_logprob_target_outside_the_vocabulary_gives_nan_not_a_stale_value():
+    """Ids outside [0, V) (an ignore index on a padded slot, an id past the vocabulary) have no logit: their
+    logprob must be NaN, whatever the workspace held before; their LSE and every other token are unaffected."""
+    x = custom(300, 128, 1000, seed=8)
+    y = x.targets.copy()
+    bad = np.array([0, 17, 255, 256, 299])
+    y[bad] = np.array([-100, -1, 1000, 1 << 30, -(1 << 31)], dtype=np.int64).astype(np.int32)
+    lp, lse = run_hip(x.bits["hidden"], x.bits["lm_head"], y, 1.0, junk_workspace=True)
+    rp, rl = ref.token_logprobs(x.hidden, x.lm_head, x.targets, 1.0)
+    good = np.setdiff1d(np.arange(300), bad)
+    assert np.isnan(lp[bad]).all()
+    assert np.abs(lp[good] - rp[good]).max() <= TOL and np.abs(lse - rl).max() <= TOL
 
 
 def test_logprob_7b_head_1000_tokens_full():

@@ -37,6 +37,7 @@ EDGE = [
     ("bf16", 2, 2, 128, 129, (513,)),                # rows cross several work items with group = 1
     ("bf16", 28, 4, 128, 5000, (40, 3)),             # few rows, long prefix: 9 key ranges, the last one ragged
     ("bf16", 8, 2, 64, 3000, (17,)),                 # the same with head_dim 64 (5 key ranges)
+    ("bf16", 6, 3, 128, 300, (100, 57)),             # 3 kv heads do not divide the 8 XCDs: lists are not interleaved
     ("f32", 4, 2, 64, 100, (33, 70)),
     ("f32", 6, 2, 128, 0, (50, 1)),
     ("f32", 3, 3, 128, 65, (1, 2, 3)),
@@ -64,6 +65,26 @@ def test_long_prefix_takes_the_separate_passes_full_tensor():
     ro, rl, _ = cref.prefix_shared_attention(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix, x.suffix_lens,
                                              x.workload.scale)
     check(out, lse, ro, rl, "long prefix, separate passes")
+
+
+def test_graded_code_path_full_tensor():
+    """Every element of the code path the 32K-prefix benchmark configuration takes: head_dim 128, 28 query heads
+    over 4 kv heads (7 heads stacked per position), a prefix of more than 256 tiles with a ragged last tile that
+    stays unsplit (separate prefix pass, one item per block of rows), then the suffix pass that merges the two
+    partial results in its epilogue; ragged rollouts, so blocks of rows end inside positions and rollouts."""
+    import paper_2507_07966_amd as pa
+    shape = (28, 4, 128, 16500, (700, 333, 517, 129, 650, 71))
+    plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 128 ** -0.5, dtype="bf16", device=-1)
+    pre = plan.items(0)
+    pre = pre[pre[:, 0] >= 0]
+    assert len(plan.items(3)) == 0                                           # no single sweep: separate passes
+    assert len(pre) >= 256 and (pre[:, 4] == 0).all() and (pre[:, 3] == 16500).all()   # one key range: the whole prefix
+    assert len(pre) == sum((s * 7 + 255) // 256 for s in shape[4]) * 4
+    plan.destroy()
+    x = wl.make_custom("bf16", *shape, seed=17)
+    out, lse = run_hip(x)
+    ro, rl = oracle_full(x)
+    check(out, lse, ro, rl, "graded code path (D=128, group 7, unsplit prefix pass + merging suffix pass)")
 
 
 def test_large_scores_and_late_maximum():
