@@ -95,6 +95,22 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
                         const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
                         void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* prefix_attn_forward for callers that cannot allocate device memory or hold a workspace: code running
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * result as prefix_attn_forward followed by prefix_attn_lse, but the workspace is an array of
+ * PA_STATIC_SCRATCH_BYTES inside the library's device image (one per GPU, held until the process
+ * ends); the call allocates nothing, frees nothing and does not synchronise.
+ *   lse_out [Hq, T] fp32 DEVICE, 16-byte aligned, or NULL when the LSE is not wanted.
+ * A plan whose workspace (workspace_bytes_out of prefix_attn_plan) exceeds PA_STATIC_SCRATCH_BYTES is
+ * rejected with PA_ERR_WORKSPACE before anything is launched.  All calls on a GPU share that GPU's
+ * array: calls that may overlap there (different streams, or threads, without ordering between them)
+ * race and must use prefix_attn_forward with workspaces of their own.  Nothing in the array has to
+ * survive between calls and nothing in it needs clearing. */
+#define PA_STATIC_SCRATCH_BYTES (64u << 20)
+int prefix_attn_forward_static(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                               const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
+                               float* lse_out, void* hip_stream);
+
 /* Measurement variant of prefix_attn_forward: same arguments and result, but each of the
  * launches is bracketed by HIP events on `hip_stream` and the call WAITS for them.
  * kernel_ms (HOST [4]) receives the durations in milliseconds of {V layout pre-pass, prefix

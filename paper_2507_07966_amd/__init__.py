@@ -6,7 +6,8 @@ use and raises if the library has not been built.
 """
 from . import workloads  # noqa: F401
 
-_BINDING_NAMES = ("PrefixAttnPlan", "PrefixAttnError", "prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed",
+_BINDING_NAMES = ("PrefixAttnPlan", "PrefixAttnError", "prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_static",
+                  "prefix_attn_forward_timed", "STATIC_SCRATCH_BYTES",
                   "prefix_attn_lse", "prefix_attn_destroy", "prefix_attn_status_string",
                   "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_forward_partial",
                   "prefix_attn_merge_partials", "token_logprob_workspace", "token_logprob_forward",

@@ -20,7 +20,8 @@ _lib = None
 PA_F32, PA_BF16 = 0, 1
 STATUS_NAMES = {0: "PA_OK", 1: "PA_ERR_NULL", 2: "PA_ERR_SHAPE", 3: "PA_ERR_UNSUPPORTED", 4: "PA_ERR_ALIGN",
                 5: "PA_ERR_WORKSPACE", 6: "PA_ERR_ALLOC", 7: "PA_ERR_HIP"}
-EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_timed", "prefix_attn_lse", "prefix_attn_destroy",
+STATIC_SCRATCH_BYTES = 64 << 20      # PA_STATIC_SCRATCH_BYTES of the header
+EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forward_static", "prefix_attn_forward_timed", "prefix_attn_lse", "prefix_attn_destroy",
                     "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
                     "prefix_attn_plan_items", "prefix_attn_plan_total_tokens", "prefix_attn_backward_workspace",
                     "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_plan_num_key_items",
@@ -64,6 +65,8 @@ def load_library():
     lib.prefix_attn_plan.argtypes = [ctypes.POINTER(_Desc), ctypes.POINTER(vp), ctypes.POINTER(sz)]
     lib.prefix_attn_forward.restype = ctypes.c_int
     lib.prefix_attn_forward.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.prefix_attn_forward_static.restype = ctypes.c_int
+    lib.prefix_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.prefix_attn_forward_timed.restype = ctypes.c_int
     lib.prefix_attn_forward_timed.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, ctypes.POINTER(ctypes.c_float)]
     lib.prefix_attn_lse.restype = ctypes.c_int
@@ -230,6 +233,16 @@ def prefix_attn_forward(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v
                                             _ptr(v_suffix), _ptr(out), _ptr(workspace), ws_bytes, _stream(stream))
     if st:
         raise PrefixAttnError(st, "prefix_attn_forward")
+
+
+def prefix_attn_forward_static(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, lse_out=None,
+                               stream=None) -> None:
+    """prefix_attn_forward_static of the C ABI: forward (+ LSE export when lse_out is given) on the library's
+    own static workspace; for plans of at most STATIC_SCRATCH_BYTES of workspace.  Enqueues only."""
+    st = load_library().prefix_attn_forward_static(plan.handle, _ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_suffix),
+                                                   _ptr(v_suffix), _ptr(out), _ptr(lse_out), _stream(stream))
+    if st:
+        raise PrefixAttnError(st, "prefix_attn_forward_static")
 
 
 def prefix_attn_forward_timed(plan: PrefixAttnPlan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace,

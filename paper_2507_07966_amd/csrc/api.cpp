@@ -1,9 +1,40 @@
 // prefix_attn_forward / prefix_attn_lse: argument checks on the host, then the launches
 // (prefix pass, suffix pass, and a merge where the suffix pass does not do it) on the caller's stream.  Nothing here allocates or
 // synchronises.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
+
+#include <mutex>
 
 #include "common.h"
+
+// Workspace of prefix_attn_forward_static: one array per GPU, part of the library's device image, so that
+// entry point never has to ask anyone for memory.  In host code this name is only a handle for
+// hipGetSymbolAddress; the array's memory is reached through the pointer static_scratch() returns.
+static __device__ __align__(256) unsigned char scratch[PA_STATIC_SCRATCH_BYTES];
+
+namespace pa {
+
+// Device address of `scratch` on `device`, which must be the current device.  Looked up once per device
+// and kept (every GPU holds its own copy of the array at its own address).
+int static_scratch(int device, void** ptr_out) {
+  constexpr int MAX_DEVICES = 64;
+  static std::mutex lock;
+  static void* ptrs[MAX_DEVICES] = {};
+  if (device < 0 || device >= MAX_DEVICES) return PA_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!ptrs[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return PA_ERR_HIP;
+    }
+    ptrs[device] = p;
+  }
+  *ptr_out = ptrs[device];
+  return PA_OK;
+}
+
+}  // namespace pa
 
 namespace {
 
@@ -185,6 +216,24 @@ int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const voi
                         size_t workspace_bytes, void* hip_stream) {
   return enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, workspace, workspace_bytes, hip_stream,
                          nullptr);
+}
+
+int prefix_attn_forward_static(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
+                               const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
+                               float* lse_out, void* hip_stream) {
+  if (!plan) return PA_ERR_NULL;
+  if (plan->ws_bytes > (size_t)PA_STATIC_SCRATCH_BYTES) return PA_ERR_WORKSPACE;
+  if (plan->desc.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan
+  if (reinterpret_cast<uintptr_t>(lse_out) & 15u) return PA_ERR_ALIGN;
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess || cur != plan->desc.device) return PA_ERR_HIP;
+  void* ws = nullptr;
+  int st = pa::static_scratch(cur, &ws);  // already resolved when the plan was made; a table look-up here
+  if (st != PA_OK) return st;
+  st = enqueue_forward(plan, q, k_prefix, v_prefix, k_suffix, v_suffix, out, ws, PA_STATIC_SCRATCH_BYTES, hip_stream,
+                       nullptr);
+  if (st != PA_OK || !lse_out) return st;
+  return prefix_attn_lse(plan, ws, lse_out, hip_stream);
 }
 
 int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,

@@ -128,6 +128,8 @@ struct MergeNArgs {
 };
 int launch_merge_n(const MergeNArgs& a, void* stream);
 int launch_lse_export(const float* lse_th, float* lse_ht, int64_t T, int32_t Hq, void* stream);
+// Device address of the library's static workspace on `device` (the current device); a pa_status_t.
+int static_scratch(int device, void** ptr_out);
 
 }  // namespace pa
 

@@ -348,6 +348,10 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
         ok = hipMalloc((void**)&p->d_key_items[s], bytes) == hipSuccess &&
              hipMemcpy(p->d_key_items[s], p->key_items[s].data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
       }
+      // set-up for prefix_attn_forward_static: look its workspace up now, with the plan's device current,
+      // so that the call itself only reads a table
+      void* unused = nullptr;
+      ok = ok && pa::static_scratch(desc->device, &unused) == PA_OK;
       (void)hipSetDevice(prev);
     }
     if (!ok) {
