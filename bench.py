@@ -88,6 +88,24 @@ def calibrate_copy(torch):
     torch.cuda.synchronize()
 
 
+RECORD = ""
+
+
+def emit(result):
+    line = json.dumps(result)
+    print(line, flush=True)
+    if RECORD:
+        with open(RECORD, "a") as f:
+            f.write(line + "\n")
+
+
+# What the `traffic` figure of a roofline block is: the committed counter summary of the same command, not a
+# quantity of this run.  FETCH_SIZE / WRITE_SIZE count bytes that cross from the L2 caches to the fabric (L2
+# misses and write-backs); the 256 MB memory-side cache may serve part of them, and no counter exposed by
+# rocprofv3 here separates its hits, so the figure is an upper bound of the HBM bytes.
+TRAFFIC_NOTE = "recorded rocprofv3 profile (profiles/), L2-miss + write-back bytes per launch: upper bound of HBM bytes"
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,10 +124,16 @@ def main():
                          "joins the shared prefix (two calls per step); also times the one-call form on the same values")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--power-probe", action="store_true",
+                    help="forward only: after the timed region run the same launches on constant inputs (all ones: the "
+                         "same instruction stream without operand toggling) and report time and shader clock of both")
+    ap.add_argument("--record", default="", metavar="FILE", help="also append the JSON line to FILE")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region also launch plain 256 MiB copy kernels (known HBM bytes, for "
                          "scaling hardware traffic counters under rocprofv3)")
     args = ap.parse_args()
+    global RECORD
+    RECORD = args.record
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1", file=sys.stderr)
         sys.exit(2)
@@ -226,7 +250,7 @@ def main():
         "rocm_smi": state,
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic(w.name, dom_name)},
+                     "traffic": measured_traffic(w.name, dom_name), "traffic_source": TRAFFIC_NOTE},
     }
 
     if not args.no_cpu_baseline:
@@ -266,7 +290,46 @@ def main():
         result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - o_ref).max()),
                                       "out_mean_abs": float(np.abs(o_gpu - o_ref).mean()),
                                       "lse_max_abs": float(np.abs(l_gpu - l_ref).max())}
-    print(json.dumps(result), flush=True)
+    if args.power_probe:
+        result["power_probe"] = power_probe(args, pa, torch, plan, dev, out, ws, lse, ms_per_step, state)
+    emit(result)
+
+
+def power_probe(args, pa, torch, plan, dev, out, ws, lse, ms_random, state_random):
+    """The same plan and launches on constant inputs: every operand of every MFMA is 1.0, so the instruction
+    stream is identical but nothing toggles in the data path.  Time and sampled shader clock of both runs show
+    how much of the step time is set by the power limit rather than by the schedule."""
+    ones = {n: torch.ones_like(t) for n, t in dev.items()}
+    P = plan.prefix_len
+    cargs = (plan, ones["q"], ones["k_prefix"] if P else None, ones["v_prefix"] if P else None, ones["k_suffix"],
+             ones["v_suffix"], out, ws)
+
+    def cstep():
+        pa.prefix_attn_forward(*cargs)
+        pa.prefix_attn_lse(plan, ws, lse)
+
+    for _ in range(args.warmup):
+        cstep()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        cstep()
+    e1.record()
+    torch.cuda.synchronize()
+    ms_const = float(e0.elapsed_time(e1) / args.steps)
+    kms = np.array([pa.prefix_attn_forward_timed(*cargs) for _ in range(args.steps)]).mean(axis=0)
+    state_const = gpu_state(torch, cstep, args.smi_as_found)
+
+    def sclk(state):
+        try:
+            return state["under_load"]["sclk clock speed"]
+        except (TypeError, KeyError):
+            return None
+    return {"random_inputs": {"ms_per_step": round(ms_random, 4), "sclk_under_load": sclk(state_random)},
+            "constant_inputs": {"ms_per_step": round(ms_const, 4), "sclk_under_load": sclk(state_const),
+                                "kernel_ms": [round(float(v), 4) for v in kms]},
+            "time_ratio_random_over_constant": round(ms_random / ms_const, 4)}
 
 
 def folded_main(args, pa, wl, torch):
@@ -329,7 +392,7 @@ def folded_main(args, pa, wl, torch):
                     for c in (prompt_call, folded_call))
     flop_one = count(w.num_q_heads, w.head_dim, w.prefix_len, x.suffix_lens)
     tflops = flop_fold / (ms_fold * 1e-3) * 1e-12
-    print(json.dumps({
+    emit({
         "metric": "effective attention backward TFLOP/s" if backward else "effective attention TFLOP/s",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_fold, 4), "higher_is_better": True,
@@ -343,7 +406,7 @@ def folded_main(args, pa, wl, torch):
                           "tflops": round(flop_one / (ms_one * 1e-3) * 1e-12, 2)},
         "time_saved_pct": round(100 * (1 - ms_fold / ms_one), 2),
         "flop_saved_pct": round(100 * (1 - flop_fold / flop_one), 2),
-    }), flush=True)
+    })
 
 
 def logprob_main(args, pa, wl, torch):
@@ -379,7 +442,7 @@ def logprob_main(args, pa, wl, torch):
         # the tile kernel is all but the microseconds of the finalize kernel
         "roofline": {"kernel": "logprob_tile", "bound": "mfma", "achieved": round(tflops, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(tflops / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic(w.name, "logprob_tile")},
+                     "traffic": measured_traffic(w.name, "logprob_tile"), "traffic_source": TRAFFIC_NOTE},
     }
     if args.calibrate_copy:
         calibrate_copy(torch)
@@ -398,7 +461,7 @@ def logprob_main(args, pa, wl, torch):
                                   "cores": int(cores), "kind": "oracle",
                                   "sample": f"{len(idx)} seeded tokens against the whole vocabulary (fp64 numpy, {t_cpu:.1f} s)"}
         result["parity_on_sample"] = {"logprob_max_abs": float(np.abs(got - rp).max())}
-    print(json.dumps(result), flush=True)
+    emit(result)
 
 
 def sharded_main(args, pa, wl, torch, w, x, dev, out, lse):
@@ -479,7 +542,7 @@ def sharded_main(args, pa, wl, torch, w, x, dev, out, lse):
                                   f"against the whole (unsharded) key set (fp64, {t_cpu:.1f} s)"}
         result["parity_on_sample"] = {"out_max_abs": float(np.abs(o_gpu - ro).max()),
                                       "lse_max_abs": float(np.abs(l_gpu - rl).max())}
-    print(json.dumps(result), flush=True)
+    emit(result)
 
 
 def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
@@ -538,7 +601,7 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
         "executed_mfma_tflops": {"dq": round(6 * w.head_dim * w.num_q_heads * pairs / (kms[1] * 1e-3) * 1e-12, 1)},
         "roofline": {"kernel": dom_name, "bound": "mfma", "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
-                     "traffic": measured_traffic(w.name, dom_name)},
+                     "traffic": measured_traffic(w.name, dom_name), "traffic_source": TRAFFIC_NOTE},
     }
     if not args.no_cpu_baseline:
         from oracle import cref
@@ -570,7 +633,7 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
                       f"sets (fp64, {t_cpu:.1f} s)", "seconds": round(t_cpu, 2)}
         result["parity_on_sample"] = {"dq_max_abs_over_rms": float(np.abs(dq_gpu - dq_ref).max() / rms),
                                       "dq_mean_abs_over_rms": float(np.abs(dq_gpu - dq_ref).mean() / rms)}
-    print(json.dumps(result), flush=True)
+    emit(result)
 
 
 if __name__ == "__main__":

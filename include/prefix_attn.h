@@ -262,7 +262,7 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
  * dQ pass: the item sweeps prefix keys [key0, key0 + pkeys) and then the rollout's own keys
  * [0, nkeys); with key ranges exactly one item of a block has nkeys > 0; the list may hold
  * padding items.
- * Single sweep (whole bf16 calls whose prefix is at most 256 tiles and not cut into key
+ * Single sweep (whole bf16 calls whose prefix is at most 1,024 tiles and not cut into key
  * ranges run as one pass per block of rows instead of prefix pass + suffix pass): like the
  * dQ pass with key0 = 0 and pkeys = P, laid out over the XCDs like the prefix pass. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);

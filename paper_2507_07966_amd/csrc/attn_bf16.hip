@@ -184,13 +184,16 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   const rsrc_t krs_own = make_rsrc(kown), vrs_own = make_rsrc(vtbase);
   const rsrc_t krs_pre = make_rsrc(SWEEP ? kpre : kown), vrs_pre = make_rsrc(SWEEP ? vtpre : vtbase);
 
-  auto issue_k = [&](int gtile, auto buf_c) {  // K tile -> K buffer buf
+  // LEAN (a compile-time flag of the sweep's prefix loop): the tile is a whole prefix tile, so neither the
+  // choice between the two key sets nor the ragged-tile path is in the instruction stream.
+  auto issue_k = [&](int gtile, auto buf_c, auto lean_c) {  // K tile -> K buffer buf
     unsigned char* dst = smem + KBUF0 + decltype(buf_c)::value * TL::KBYTES;
-    const bool pre = SWEEP && gtile < tp;
+    constexpr bool LEAN = decltype(lean_c)::value;
+    const bool pre = LEAN || (SWEEP && gtile < tp);
     const int tile = pre ? gtile : gtile - tp;       // tile index inside its key set
     const int set_keys = pre ? P : nkeys;            // keys of that set
     const __bf16* kbase = pre ? kpre : kown;
-    if (tile < set_keys / BN) {                      // all 64 keys exist
+    if (LEAN || tile < set_keys / BN) {              // all 64 keys exist
       const unsigned soff = (unsigned)(tile * ktile_bytes);
 #pragma unroll
       for (int n = 0; n < TL::KBLOCKS_PER_WAVE; ++n) {
@@ -210,9 +213,9 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     }
   };
   const unsigned voffs = (unsigned)(((wave * TL::VBLOCKS_PER_WAVE) * 512 + lane * 8) * 2);
-  auto issue_v = [&](int gtile, auto buf_c) {  // V^T image -> V buffer buf (a linear copy)
+  auto issue_v = [&](int gtile, auto buf_c, auto lean_c) {  // V^T image -> V buffer buf (a linear copy)
     unsigned char* dst = smem + VBUF0 + decltype(buf_c)::value * TL::VBYTES;
-    const bool pre = SWEEP && gtile < tp;
+    const bool pre = decltype(lean_c)::value || (SWEEP && gtile < tp);
     const unsigned soff = (unsigned)((pre ? gtile : gtile - tp) * (D * BN * 2));
 #pragma unroll
     for (int n = 0; n < TL::VBLOCKS_PER_WAVE; ++n) {
@@ -359,10 +362,11 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     }
   };
 
+  using GENERAL = std::false_type;
   // ---- prologue: tiles 0 (and K of tile 1) in flight; scores and softmax of tile 0
-  issue_k(0, B0{});
-  issue_v(0, B0{});
-  if (ntiles > 1) issue_k(1, B1{});
+  issue_k(0, B0{}, GENERAL{});
+  issue_v(0, B0{}, GENERAL{});
+  if (ntiles > 1) issue_k(1, B1{}, GENERAL{});
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
   __syncthreads();
   scores(smem + KBUF0, [](int) {});
@@ -380,13 +384,16 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
 
   // ---- steady state, step t >= 1 (BUF = t & 1): scores of tile t, then PV of tile t-1 on the
   //      MFMA pipe interleaved with the softmax of tile t on the VALU.
-  auto step = [&](int t, auto buf_c) {
+  //      LEAN steps (sweep only) are those whose tiles t and t + 1 are both whole prefix tiles: no mask, no
+  //      choice of key set, no bounds on t.
+  auto step = [&](int t, auto buf_c, auto lean_c) {
     constexpr int BUF = decltype(buf_c)::value;
+    constexpr bool LEAN = decltype(lean_c)::value;
     scores(smem + KBUF0 + BUF * TL::KBYTES, [&](int kk) {
-      if (kk == KK / 8 && t + 1 < ntiles) issue_k(t + 1, std::integral_constant<int, BUF ^ 1>{});
-      if (kk == KK / 2 + KK / 8) issue_v(t, std::integral_constant<int, BUF>{});
+      if (kk == KK / 8 && (LEAN || t + 1 < ntiles)) issue_k(t + 1, std::integral_constant<int, BUF ^ 1>{}, lean_c);
+      if (kk == KK / 2 + KK / 8) issue_v(t, std::integral_constant<int, BUF>{}, lean_c);
     });
-    mask_scores(S, t);
+    if (!LEAN) mask_scores(S, t);
     bf16x8 Pn[4];
     float lacc[2] = {0.f, 0.f};
     pv(smem + VBUF0 + (BUF ^ 1) * TL::VBYTES, std::true_type{}, Pn, lacc);
@@ -396,11 +403,18 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
   };
   {
     int t = 1;
-    for (; t + 1 < ntiles; t += 2) {
-      step(t, B1{});
-      step(t + 1, B0{});
+    if constexpr (SWEEP) {  // pairs of steps inside the prefix, away from its last tile (which may be ragged)
+      const int lean_end = P / BN - 1;  // steps t <= lean_end - 1 have tiles t and t + 1 whole and in the prefix
+      for (; t + 1 < lean_end; t += 2) {
+        step(t, B1{}, std::true_type{});
+        step(t + 1, B0{}, std::true_type{});
+      }
     }
-    if (t < ntiles) step(t, B1{});
+    for (; t + 1 < ntiles; t += 2) {
+      step(t, B1{}, GENERAL{});
+      step(t + 1, B0{}, GENERAL{});
+    }
+    if (t < ntiles) step(t, B1{}, GENERAL{});
   }
   // ---- drain: PV of the last tile
   {

@@ -55,17 +55,30 @@ def check(out, lse, ref_out, ref_lse, label=""):
 
 
 GRAD_NAMES = ("dq", "dk_prefix", "dv_prefix", "dk_suffix", "dv_suffix")
-# Gradient tolerances.  An element may be off by
-#   |err| <= GRAD_REL * |ref| + GRAD_ABS_RMS * rms(ref),   and   mean|err| <= GRAD_MEAN_RMS * rms(ref).
-# bf16 path: (1) every gradient is rounded to bf16 once at the end: relative 2^-9 of the element
-# (GRAD_REL leaves a factor 2); (2) the weights W and dS are rounded to bf16 before the two
-# accumulating products: independent relative 2^-9 errors, a few 1e-3 of the tensor's rms after
-# summation; (3) delta = <dO, O> is taken from the bf16-rounded forward output, which perturbs
-# every dS of a row by W * (2^-9-level error of a length-D dot product); it matters for rows that
-# see only a few keys, where it reaches a few percent of the tensor's rms.  The mean bound is the
-# sharp one (an ideal rounding of the exact gradient alone gives about 1.1e-3 rms).
+# Gradient tolerances, from the rounding model of the bf16 path.  Every gradient vector (one token or key, one
+# head, D channels) is a sum  y_d = sum_k a_k b_kd  whose factor a_k (a softmax weight W or a dS) was rounded to
+# bf16 first: independent relative errors uniform in [-u, u], u = 2^-9.  Its error therefore has standard
+# deviation (u / sqrt 3) sqrt(sum_k a_k^2 b_kd^2), and for factors b of mixed sign that root is the size of the
+# vector's own elements: sigma = 1.1e-3 of the vector's root-mean-square, 6 sigma = 7e-3 at the largest of 1e8
+# elements (measured: 6e-3 ... 1.2e-2 on iid inputs, 1.7e-2 where all keys of a head share a mean vector, which
+# cancels in the exact sum but not in the rounding errors).  The final rounding of the result adds u |y_d|.
+# An element may therefore be off by
+#   |err| <= GRAD_REL |ref| + GRAD_VEC rms(its vector) + GRAD_FLOOR rms(tensor),
+# with GRAD_REL = 2 u, GRAD_VEC = 2^-5 (2.5 times the largest measured value), and the mean error by
+# GRAD_MEAN_RMS rms(tensor) (an ideal rounding of the exact gradient alone gives 1.1e-3).
+# The floor covers vectors that are small by cancellation, where the model's "own size" is not the error's
+# scale: delta = <dO, O> is taken from the bf16-rounded forward output, an absolute error of about
+# (u / sqrt 3) sqrt(D) rms(dO) rms(O) on every dS of the row times its weight.  It is negligible next to the
+# vector term once a row sees many keys (|O| ~ 1 / sqrt(keys)); for a key seen by a single row (rank-one dK) it
+# reaches 2e-3 of the tensor's rms (floor 2^-7); for rows that see one or two keys, whose exact dQ cancels to
+# (almost) zero, it is 8 (u / sqrt 3) rms(dO) rms(V) max|K| = 3e-2 absolute at N(0,1) inputs, measured 3.1e-2 of
+# the tensor's rms (floor 2^-4, used only when some row sees fewer than FEW_KEYS keys).
+# fp32 path: fp32 rounding throughout.
 GRAD_REL = {"bf16": 2.0 ** -8, "f32": 1e-5}
-GRAD_ABS_RMS = {"bf16": 8e-2, "f32": 1e-4}
+GRAD_VEC = {"bf16": 2.0 ** -5, "f32": 1e-4}
+GRAD_FLOOR = {"bf16": 2.0 ** -7, "f32": 1e-4}
+GRAD_FLOOR_FEW_KEYS = {"bf16": 2.0 ** -4, "f32": 1e-4}
+FEW_KEYS = 8
 GRAD_MEAN_RMS = {"bf16": 3e-3, "f32": 1e-5}
 
 
@@ -102,28 +115,28 @@ def run_hip_backward(x, d_out, d_out_bits=None, scale=None, keep=False):
     return res
 
 
-def check_grad_tensor(a, r, dtype, label=""):
-    """One gradient tensor `a` against the oracle's `r` (same shape, last axis = head_dim).  Returns the worst
-    element error in units of the tensor's rms."""
+def check_grad_tensor(a, r, dtype, label="", min_visible_keys=1 << 30):
+    """One gradient tensor `a` against the oracle's `r` (same shape, last axis = head_dim).  min_visible_keys:
+    the smallest number of keys any query row of the call sees (prefix_len + 1).  Returns the worst element
+    error in units of its tolerance."""
     assert a.shape == r.shape, f"{label}: shape {a.shape} vs {r.shape}"
     if r.size == 0:
         return 0.0
     assert np.isfinite(a).all(), f"{label}: non-finite gradient"
     rms = float(np.sqrt(np.mean(r * r)))
     d = np.abs(a - r)
-    row = np.sqrt(np.mean(r * r, axis=-1, keepdims=True))        # rms of each (token, head) vector
-    excess = np.maximum(d - GRAD_REL[dtype] * np.abs(r), 0.0)
-    in_row_units = float((excess / np.maximum(row, 1e-3 * rms + 1e-300)).max())
-    beyond = float(np.maximum(excess - 2.0 ** -5 * row, 0.0).max() / max(rms, 1e-300))
-    msg = (f"{label}: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (reference rms {rms:.3e}); worst element "
-           f"{d.max() / max(rms, 1e-300):.3e} of the tensor's rms, {in_row_units:.3e} of its vector's rms, "
-           f"beyond {beyond:.3e}")
+    vec = np.sqrt(np.mean(r * r, axis=-1, keepdims=True))        # rms of each (token or key, head) vector
+    floor = (GRAD_FLOOR_FEW_KEYS if min_visible_keys < FEW_KEYS else GRAD_FLOOR)[dtype]
+    tol = GRAD_REL[dtype] * np.abs(r) + GRAD_VEC[dtype] * vec + floor * rms + 1e-30
+    worst = float((d / tol).max())
+    msg = (f"{label}: max-abs {d.max():.3e} mean-abs {d.mean():.3e} (reference rms {rms:.3e}); worst element at "
+           f"{worst:.2f} of its tolerance, mean at {d.mean() / (GRAD_MEAN_RMS[dtype] * rms + 1e-30):.2f}")
     print(msg, flush=True)
-    assert (d <= GRAD_REL[dtype] * np.abs(r) + GRAD_ABS_RMS[dtype] * rms + 1e-30).all(), msg
+    assert worst <= 1.0, msg
     assert d.mean() <= GRAD_MEAN_RMS[dtype] * rms + 1e-30, msg
-    return d.max() / max(rms, 1e-30)
+    return worst
 
 
-def check_grads(got, ref, dtype, label=""):
+def check_grads(got, ref, dtype, label="", min_visible_keys=1 << 30):
     """got: dict from run_hip_backward; ref: the oracle's five arrays in GRAD_NAMES order."""
-    return max(check_grad_tensor(got[n], r, dtype, f"{label} {n}") for n, r in zip(GRAD_NAMES, ref))
+    return max(check_grad_tensor(got[n], r, dtype, f"{label} {n}", min_visible_keys) for n, r in zip(GRAD_NAMES, ref))

@@ -52,13 +52,13 @@ def test_backward_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
     do, bits = wl.make_d_out(x)
     print(f"backward edge case {dtype} Hq={Hq} Hkv={Hkv} D={D} P={P} lens={lens}", flush=True)
     got = run_hip_backward(x, do, bits)
-    check_grads(got, oracle_backward(x, do), dtype, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
+    check_grads(got, oracle_backward(x, do), dtype, f"edge {dtype} {Hq}/{Hkv}/{D} P={P} {lens}", P + 1)
     # also against the plain definition (numpy: chain rule on the forward formula, softmax Jacobian written out),
     # which has none of the two-phase structure that the C version shares with the kernels
     if Hq * sum(lens) * (P + max(lens)) <= 3e7:
         plain = ref.prefix_shared_attention_backward(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
                                                      x.suffix_lens, x.workload.scale, do)
-        check_grads(got, plain, dtype, f"edge vs the plain definition {dtype} {Hq}/{Hkv}/{D} P={P} {lens}")
+        check_grads(got, plain, dtype, f"edge vs the plain definition {dtype} {Hq}/{Hkv}/{D} P={P} {lens}", P + 1)
 
 
 @pytest.mark.parametrize("Hq,Hkv,D,P,lens", [(28, 4, 128, 500, (300, 129)), (8, 2, 64, 300, (1500, 700, 1))])

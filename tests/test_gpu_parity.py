@@ -54,11 +54,13 @@ def test_edge_shapes_full_tensor(dtype, Hq, Hkv, D, P, lens):
 
 
 def test_long_prefix_takes_the_separate_passes_full_tensor():
-    """A prefix of more than 256 tiles with enough rows to leave it unsplit: prefix pass, then the suffix pass
-    that merges in its epilogue (shorter prefixes run as one sweep); ragged, full tensor."""
+    """A prefix of more than 1,024 tiles with enough rows to leave it unsplit: prefix pass, then the suffix pass
+    that merges in its epilogue (shorter prefixes run as one sweep); head_dim 64, one head per kv head, ragged,
+    full tensor."""
     import paper_2507_07966_amd as pa
-    shape = (4, 4, 64, 16448, (3000, 2500, 2756))
+    shape = (4, 4, 64, 65600, (3000, 2500, 2756))
     plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 0.125, dtype="bf16", device=-1)
+    assert len(plan.items(3)) == 0
     assert len(plan.items(0)) >= 129 and len(set(plan.items(0)[:, 4].tolist())) == 1        # unsplit prefix keys
     x = wl.make_custom("bf16", *shape, seed=13)
     out, lse = run_hip(x)
@@ -69,22 +71,39 @@ def test_long_prefix_takes_the_separate_passes_full_tensor():
 
 def test_graded_code_path_full_tensor():
     """Every element of the code path the 32K-prefix benchmark configuration takes: head_dim 128, 28 query heads
-    over 4 kv heads (7 heads stacked per position), a prefix of more than 256 tiles with a ragged last tile that
-    stays unsplit (separate prefix pass, one item per block of rows), then the suffix pass that merges the two
-    partial results in its epilogue; ragged rollouts, so blocks of rows end inside positions and rollouts."""
+    over 4 kv heads (7 heads stacked per position), an unsplit prefix of more than 256 tiles with a ragged last
+    tile, swept together with each block's own keys in one launch (the prefix part in the loop that carries no
+    mask and no choice of key set); ragged rollouts, so blocks of rows end inside positions and rollouts."""
     import paper_2507_07966_amd as pa
     shape = (28, 4, 128, 16500, (700, 333, 517, 129, 650, 71))
     plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 128 ** -0.5, dtype="bf16", device=-1)
-    pre = plan.items(0)
-    pre = pre[pre[:, 0] >= 0]
-    assert len(plan.items(3)) == 0                                           # no single sweep: separate passes
-    assert len(pre) >= 256 and (pre[:, 4] == 0).all() and (pre[:, 3] == 16500).all()   # one key range: the whole prefix
-    assert len(pre) == sum((s * 7 + 255) // 256 for s in shape[4]) * 4
+    sw = plan.items(3)
+    sw = sw[sw[:, 0] >= 0]
+    assert len(sw) == sum((s * 7 + 255) // 256 for s in shape[4]) * 4 >= 256      # every block of rows once
+    assert (sw[:, 4] == 0).all() and (sw[:, 5] == 16500).all()                    # each sweeps the whole prefix
     plan.destroy()
     x = wl.make_custom("bf16", *shape, seed=17)
     out, lse = run_hip(x)
     ro, rl = oracle_full(x)
-    check(out, lse, ro, rl, "graded code path (D=128, group 7, unsplit prefix pass + merging suffix pass)")
+    check(out, lse, ro, rl, "graded code path (D=128, group 7, one sweep over a 16.5K prefix and the own keys)")
+
+
+def test_separate_passes_d128_group7_full_tensor():
+    """The path of the hour-long and max-frame configurations, element by element: a prefix of more than 1,024
+    tiles (ragged last tile) stays unsplit and runs as prefix pass + suffix pass with the merging epilogue,
+    head_dim 128, 7 heads per kv head, ragged rollouts."""
+    import paper_2507_07966_amd as pa
+    shape = (28, 4, 128, 65700, (400, 333, 267, 200))
+    plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), 128 ** -0.5, dtype="bf16", device=-1)
+    pre = plan.items(0)
+    pre = pre[pre[:, 0] >= 0]
+    assert len(plan.items(3)) == 0                                                # no single sweep
+    assert len(pre) == 140 and (pre[:, 4] == 0).all() and (pre[:, 3] == 65700).all()   # one key range: the whole prefix
+    plan.destroy()
+    x = wl.make_custom("bf16", *shape, seed=23)
+    out, lse = run_hip(x)
+    ro, rl = oracle_full(x)
+    check(out, lse, ro, rl, "separate passes (D=128, group 7, unsplit 65.7K prefix + merging suffix pass)")
 
 
 def test_large_scores_and_late_maximum():

@@ -53,7 +53,7 @@ def test_c4_hour_long_sampled_rows():
 
 
 def test_c5_max_frames_ragged_sampled_rows():
-    x, out, lse = sampled_parity("C5", n_random=1, stride=1024, item_bounds=1)
+    x, out, lse = sampled_parity("C5", n_random=1, stride=2048, item_bounds=1)
     assert len(set(x.suffix_lens.tolist())) > 8   # really ragged
 
 

@@ -160,7 +160,7 @@ def test_schedule_covers_random_shapes(Hq, Hkv, D, P, lens):
 
 
 def test_single_sweep_list_only_for_short_unsplit_prefixes():
-    """Whole bf16 calls with a prefix of at most 256 tiles run one sweep per block of rows: the list holds every
+    """Whole bf16 calls with a prefix of at most 1,024 tiles run one sweep per block of rows: the list holds every
     block of the suffix list once, with the whole prefix, one kv head per XCD subset."""
     plan = host_plan()                                                                  # P = 4,096: 64 tiles
     sweep, suffix = plan.items(3), plan.items(1)
@@ -169,7 +169,8 @@ def test_single_sweep_list_only_for_short_unsplit_prefixes():
     assert (real[:, 4] == 0).all() and (real[:, 5] == 4096).all()
     for x in range(8):
         assert len({int(it[2]) for it in sweep[x::8] if it[0] >= 0}) == 1
-    assert len(host_plan(prefix_len=32768, suffix_lens=[2304] * 8).items(3)) == 0       # 512 tiles: separate passes
+    assert len(host_plan(prefix_len=32768, suffix_lens=[2304] * 8).items(3)) == 2016    # 512 tiles: still one sweep
+    assert len(host_plan(prefix_len=230400, suffix_lens=[2304] * 8).items(3)) == 0      # 3,600 tiles: separate passes
     assert len(host_plan(prefix_len=4096, suffix_lens=[256]).items(3)) == 0             # few rows: key ranges instead
     assert len(host_plan(dtype="f32").items(3)) == 0
     assert len(host_plan(prefix_len=0).items(3)) == 0

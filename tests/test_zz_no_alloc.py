@@ -35,7 +35,7 @@ def run_static(x):
 
 @pytest.mark.gpu
 def test_static_workspace_forward_two_calls_second_smaller():
-    cases = [wl.make_custom("bf16", 4, 4, 64, 16448, (3000, 2500, 2756), seed=40),   # prefix pass + merging suffix pass
+    cases = [wl.make_custom("bf16", 2, 2, 64, 65600, (4000, 2500, 3756), seed=40),   # prefix pass + merging suffix pass
              wl.make_custom("bf16", 28, 4, 128, 700, (300, 129, 77), seed=41),       # smaller: one sweep
              wl.make_custom("bf16", 28, 4, 128, 5000, (40, 3), seed=42),             # prefix key ranges + n-way merge
              wl.make_custom("f32", 4, 2, 64, 100, (33, 70), seed=43)]                # fp32: stand-alone merge kernel
