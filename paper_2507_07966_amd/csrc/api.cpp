@@ -239,7 +239,8 @@ int prefix_attn_forward_static(const prefix_attn_plan_t* plan, const void* q, co
 int prefix_attn_forward_timed(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                               const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,
                               void* workspace, size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
-  if (!kernel_ms) return PA_ERR_NULL;
+  if (!plan || !kernel_ms) return PA_ERR_NULL;
+  if (plan->desc.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan: no events either
   hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
   int st = PA_OK;
   for (int i = 0; i < 5 && st == PA_OK; ++i)

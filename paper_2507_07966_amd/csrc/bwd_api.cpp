@@ -213,7 +213,8 @@ int prefix_attn_backward_timed(const prefix_attn_plan_t* plan, const void* q, co
                                const void* d_out, const float* lse, void* dq, void* dk_prefix,
                                void* dv_prefix, void* dk_suffix, void* dv_suffix, void* workspace,
                                size_t workspace_bytes, void* hip_stream, float* kernel_ms) {
-  if (!kernel_ms) return PA_ERR_NULL;
+  if (!plan || !kernel_ms) return PA_ERR_NULL;
+  if (plan->desc.device < 0) return PA_ERR_UNSUPPORTED;  // host-only plan: no events either
   const BackwardArgs x{q,  k_prefix,  v_prefix,  k_suffix,  v_suffix,  out,       d_out,          lse,
                        dq, dk_prefix, dv_prefix, dk_suffix, dv_suffix, workspace, workspace_bytes};
   hipEvent_t ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
