@@ -125,8 +125,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--power-probe", action="store_true",
-                    help="forward only: after the timed region run the same launches on constant inputs (all ones: the "
-                         "same instruction stream without operand toggling) and report time and shader clock of both")
+                    help="after the timed region run the same launches on constant inputs (the same instruction stream "
+                         "without operand toggling) and report time and shader clock of both")
     ap.add_argument("--record", default="", metavar="FILE", help="also append the JSON line to FILE")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="after the timed region also launch plain 256 MiB copy kernels (known HBM bytes, for "
@@ -446,6 +446,25 @@ def logprob_main(args, pa, wl, torch):
     }
     if args.calibrate_copy:
         calibrate_copy(torch)
+    if args.power_probe:   # the same launch on constant inputs (see power_probe)
+        state_r = gpu_state(torch, lambda: pa.token_logprob_forward(h, W, y, 1.0, lp, lse, ws), args.smi_as_found)
+        h1, W1 = torch.ones_like(h), torch.full_like(W, 2.0 ** -6)
+        lp1, lse1 = torch.empty_like(lp), torch.empty_like(lse)
+        cstep = lambda: pa.token_logprob_forward(h1, W1, y, 1.0, lp1, lse1, ws)
+        for _ in range(args.warmup):
+            cstep()
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(args.steps):
+            cstep()
+        c1.record()
+        torch.cuda.synchronize()
+        state_c = gpu_state(torch, cstep, args.smi_as_found)
+        sclk = lambda st: st["under_load"].get("sclk clock speed") if st and st.get("under_load") else None
+        result["power_probe"] = {"random_inputs": {"ms_per_step": round(ms, 4), "sclk_under_load": sclk(state_r)},
+                                 "constant_inputs": {"ms_per_step": round(float(c0.elapsed_time(c1) / args.steps), 4),
+                                                     "sclk_under_load": sclk(state_c)}}
     if not args.no_cpu_baseline:
         from oracle import ref_logprob
         idx = np.sort(np.random.default_rng(4).choice(N, size=min(N, 64), replace=False))
@@ -578,6 +597,27 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
     kms = np.array([pa.prefix_attn_backward_timed(*bargs) for _ in range(args.steps)]).mean(axis=0)
     if args.calibrate_copy:
         calibrate_copy(torch)
+    probe = None
+    if args.power_probe:   # the same launches with every tensor set to 1.0 (see power_probe)
+        state_r = gpu_state(torch, lambda: pa.prefix_attn_backward(*bargs), args.smi_as_found)
+        cargs = tuple(torch.ones_like(t) if i in (1, 2, 3, 4, 5, 6, 7) and t is not None else t for i, t in enumerate(bargs))
+        cargs = cargs[:8] + (torch.zeros_like(lse),) + cargs[9:]      # LSE of all-equal scores is not needed exactly
+        for _ in range(args.warmup):
+            pa.prefix_attn_backward(*cargs)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(args.steps):
+            pa.prefix_attn_backward(*cargs)
+        c1.record()
+        torch.cuda.synchronize()
+        ckms = np.array([pa.prefix_attn_backward_timed(*cargs) for _ in range(args.steps)]).mean(axis=0)
+        state_c = gpu_state(torch, lambda: pa.prefix_attn_backward(*cargs), args.smi_as_found)
+        sclk = lambda st: st["under_load"].get("sclk clock speed") if st and st.get("under_load") else None
+        probe = {"random_inputs": {"ms_per_step": round(ms_per_step, 4), "sclk_under_load": sclk(state_r),
+                                   "kernel_ms": [round(float(v), 4) for v in kms]},
+                 "constant_inputs": {"ms_per_step": round(float(c0.elapsed_time(c1) / args.steps), 4),
+                                     "sclk_under_load": sclk(state_c), "kernel_ms": [round(float(v), 4) for v in ckms]}}
     pairs = wl.visible_pairs(P, x.suffix_lens)
     flop = wl.backward_flop(w.num_q_heads, w.head_dim, P, x.suffix_lens)
     tflops = flop / (ms_per_step * 1e-3) * 1e-12
@@ -633,6 +673,8 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
                       f"sets (fp64, {t_cpu:.1f} s)", "seconds": round(t_cpu, 2)}
         result["parity_on_sample"] = {"dq_max_abs_over_rms": float(np.abs(dq_gpu - dq_ref).max() / rms),
                                       "dq_mean_abs_over_rms": float(np.abs(dq_gpu - dq_ref).mean() / rms)}
+    if probe:
+        result["power_probe"] = probe
     emit(result)
 
 
