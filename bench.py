@@ -122,6 +122,9 @@ def main():
     ap.add_argument("--fold-prompt", action="store_true",
                     help="two-level sharing: the rollouts share their question, so the prompt is computed once and "
                          "joins the shared prefix (two calls per step); also times the one-call form on the same values")
+    ap.add_argument("--prefix-frames", type=int, default=-1, metavar="F",
+                    help="forward/backward: run the workload with a video prefix of F frames instead of its own "
+                         "(same rollouts; for measuring how time depends on the prefix length)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
     ap.add_argument("--power-probe", action="store_true",
@@ -156,6 +159,10 @@ def main():
         return folded_main(args, pa, wl, torch)
 
     w = wl.WORKLOADS[args.workload]
+    if args.prefix_frames >= 0:
+        import dataclasses
+        w = dataclasses.replace(w, frames=args.prefix_frames, name=f"{w.name}@{args.prefix_frames}frames",
+                                note=f"{w.note}; prefix changed to {args.prefix_frames} frames")
     x = wl.make_inputs(w)
     T, P = x.total_suffix, w.prefix_len
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
