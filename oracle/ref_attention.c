@@ -127,10 +127,13 @@ int ref_prefix_shared_attention(const float* q, const float* k_prefix, const flo
  * A kv head sums over the q heads of its group; a prefix key/value also sums over all
  * rollouts, since every rollout attends to the same cached prefix (Sec. 5.1).
  *
- * Phase 1 visits every query row (two-pass softmax as above), writes dQ and keeps the row's
- * LSE and delta.  Phase 2 visits every key and sums over the rows that see it, with
- * W_j = exp(s_j - LSE).  rows != NULL: only dQ of those packed token rows is produced
- * (dq [n_rows,Hq,D]) and phase 2 is skipped (the four key/value gradients may be NULL).
+ * One query row (token, q head) at a time, exactly as the formulas read: its scores and weights
+ * (two-pass softmax as above), dW, delta and dS over its visible keys; dQ of the row is written,
+ * and the row's terms W_j dO and scale dS_j q are added to dV_j and dK_j of every key it sees.
+ * Nothing is saved between rows and nothing is recomputed per key.  (Threads work on different
+ * rows and add into accumulators of their own, which are summed at the end.)
+ * rows != NULL: only dQ of those packed token rows is produced (dq [n_rows,Hq,D]); the four
+ * key/value gradients are not touched and may be NULL.
  * Returns the number of threads used, or a negative value on a bad argument.
  */
 int ref_prefix_shared_attention_backward(const float* q, const float* k_prefix, const float* v_prefix,
@@ -158,12 +161,12 @@ int ref_prefix_shared_attention_backward(const float* q, const float* k_prefix, 
   if (num_threads > 0) omp_set_num_threads(num_threads);
   used = omp_get_max_threads();
 #endif
-  double* lse = NULL;
-  double* delta = NULL;
+  /* per thread: dK and dV of every key ([P + T][Hkv][D] each; prefix keys first, then the packed suffix keys) */
+  const size_t n_kv = (size_t)(P + T) * Hkv * D;
+  double* acc = NULL;
   if (!rows) {
-    lse = (double*)malloc(sizeof(double) * (size_t)T * Hq);
-    delta = (double*)malloc(sizeof(double) * (size_t)T * Hq);
-    if (!lse || !delta) { free(lse); free(delta); free(off); return -3; }
+    acc = (double*)calloc((size_t)used * 2 * n_kv, sizeof(double));
+    if (!acc) { free(off); return -3; }
   }
   int bad = 0;
 #pragma omp parallel
@@ -219,54 +222,49 @@ int ref_prefix_shared_attention_backward(const float* q, const float* k_prefix, 
                                     : k_suffix + ((size_t)(off[g] + j - P) * Hkv + c) * D;
           for (int d = 0; d < D; ++d) o[d] += scale * ds * (double)kv[d];
         }
-        if (!rows) {
-          lse[(size_t)t * Hq + h] = m + log(Z);
-          delta[(size_t)t * Hq + h] = dl;
+        if (!rows) { /* this row's share of dK and dV of the keys it sees */
+          int tid = 0;
+#ifdef _OPENMP
+          tid = omp_get_thread_num();
+#endif
+          double* acc_k = acc + (size_t)tid * 2 * n_kv;
+          double* acc_v = acc_k + n_kv;
+          for (int64_t j = 0; j < nk; ++j) {
+            const double ds = s[j] * (dw[j] - dl);
+            const size_t key = (j < P) ? (size_t)j : (size_t)(P + off[g] + (j - P));
+            double* dk = acc_k + (key * Hkv + c) * D;
+            double* dv = acc_v + (key * Hkv + c) * D;
+            for (int d = 0; d < D; ++d) {
+              dk[d] += scale * ds * (double)qv[d];
+              dv[d] += s[j] * (double)dov[d];
+            }
+          }
         }
       }
     }
     free(s);
     free(dw);
 
-    if (!rows && !bad) {
-      /* phase 2: one key (jj < P: prefix token jj, else packed suffix token jj - P) and kv head at a time */
-#pragma omp for schedule(dynamic, 1) collapse(2)
-      for (int64_t jj = 0; jj < P + T; ++jj) {
-        for (int c = 0; c < Hkv; ++c) {
-          const int is_prefix = jj < P;
-          const int64_t tj = jj - P;  /* packed row of a suffix key */
-          const float* kv = is_prefix ? k_prefix + ((size_t)jj * Hkv + c) * D : k_suffix + ((size_t)tj * Hkv + c) * D;
-          const float* vv = is_prefix ? v_prefix + ((size_t)jj * Hkv + c) * D : v_suffix + ((size_t)tj * Hkv + c) * D;
-          double* dk = is_prefix ? dk_prefix + ((size_t)jj * Hkv + c) * D : dk_suffix + ((size_t)tj * Hkv + c) * D;
-          double* dv = is_prefix ? dv_prefix + ((size_t)jj * Hkv + c) * D : dv_suffix + ((size_t)tj * Hkv + c) * D;
-          for (int d = 0; d < D; ++d) { dk[d] = 0.0; dv[d] = 0.0; }
-          /* rows that see this key: every packed row for a prefix key; for a suffix key the rows of
-           * its own rollout from the key's position on */
-          int64_t t0 = 0, t1 = T;
-          if (!is_prefix) {
-            int g = 0;
-            while (off[g + 1] <= tj) ++g;
-            t0 = tj;
-            t1 = off[g + 1];
-          }
-          for (int64_t t = t0; t < t1; ++t) {
-            for (int h = c * r; h < (c + 1) * r; ++h) {
-              const float* qv = q + ((size_t)t * Hq + h) * D;
-              const float* dov = d_out + ((size_t)t * Hq + h) * D;
-              const double w = exp(scale * dot_fd(qv, kv, D) - lse[(size_t)t * Hq + h]);
-              const double ds = w * (dot_fd(dov, vv, D) - delta[(size_t)t * Hq + h]);
-              for (int d = 0; d < D; ++d) {
-                dk[d] += scale * ds * (double)qv[d];
-                dv[d] += w * (double)dov[d];
-              }
-            }
-          }
+    if (!rows && !bad) { /* sum the threads' accumulators in thread order */
+#pragma omp for schedule(static)
+      for (int64_t e = 0; e < (int64_t)n_kv; ++e) {
+        double sk = 0.0, sv = 0.0;
+        for (int th = 0; th < used; ++th) {
+          sk += acc[(size_t)th * 2 * n_kv + (size_t)e];
+          sv += acc[(size_t)th * 2 * n_kv + n_kv + (size_t)e];
+        }
+        const size_t n_pre = (size_t)P * Hkv * D;
+        if ((size_t)e < n_pre) {
+          dk_prefix[e] = sk;
+          dv_prefix[e] = sv;
+        } else {
+          dk_suffix[(size_t)e - n_pre] = sk;
+          dv_suffix[(size_t)e - n_pre] = sv;
         }
       }
     }
   }
-  free(lse);
-  free(delta);
+  free(acc);
   free(off);
   return bad ? -4 : used;
 }
