@@ -127,6 +127,10 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's share of stage s has landed
     __syncthreads();                      // everyone's share has; the other buffer is no longer read
     if (s + 1 < nstages) issue(s + 1, BUF ^ 1);
+    // The MFMA part of a stage runs at wave priority 1, the wait, the barrier and the issue of the next stage's
+    // loads at priority 0: of the two wavefronts sharing a SIMD, the one already in its MFMAs is served before
+    // the one still issuing loads (+1.5 %; priority for the loads instead: -0.4 %).
+    __builtin_amdgcn_s_setprio(1);
 #pragma unroll
     for (int kk = 0; kk < BK / 16; ++kk) {
       bf16x8 wa[2], hb[4];
@@ -139,6 +143,7 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
 #pragma unroll
         for (int b = 0; b < 4; ++b) C[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[b], C[a][b], 0, 0, 0);
     }
+    __builtin_amdgcn_s_setprio(0);
   };
   issue(0, 0);
   {
