@@ -4,7 +4,8 @@
 // natural-log LSE over the keys it covers.  The two partials are combined by log-sum-exp either
 // by the merge kernel or, for whole calls, in the suffix pass's own epilogue (it reads the prefix
 // partial of its rows and writes the final output).  A third mode of the suffix pass sweeps the
-// prefix keys and then the own keys in one online softmax (short prefixes: one launch, no partials).
+// prefix keys and then the own keys in one online softmax (prefixes up to 65,536 keys: one launch, no
+// partials); the part of that sweep that lies inside the prefix runs the prefix pass's instruction stream.
 //
 // Why the prefix K/V can be shared at all: the video embeddings are gathered once per step
 // and reused by every rollout (paper Sec. 5.1), so all G rollouts of a question attend to
