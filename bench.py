@@ -604,7 +604,7 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
     kms = np.array([pa.prefix_attn_backward_timed(*bargs) for _ in range(args.steps)]).mean(axis=0)
     if args.calibrate_copy:
         calibrate_copy(torch)
-    probe = None
+    power = None
     if args.power_probe:   # the same launches with every tensor set to 1.0 (see power_probe)
         state_r = gpu_state(torch, lambda: pa.prefix_attn_backward(*bargs), args.smi_as_found)
         cargs = tuple(torch.ones_like(t) if i in (1, 2, 3, 4, 5, 6, 7) and t is not None else t for i, t in enumerate(bargs))
@@ -621,7 +621,7 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
         ckms = np.array([pa.prefix_attn_backward_timed(*cargs) for _ in range(args.steps)]).mean(axis=0)
         state_c = gpu_state(torch, lambda: pa.prefix_attn_backward(*cargs), args.smi_as_found)
         sclk = lambda st: st["under_load"].get("sclk clock speed") if st and st.get("under_load") else None
-        probe = {"random_inputs": {"ms_per_step": round(ms_per_step, 4), "sclk_under_load": sclk(state_r),
+        power = {"random_inputs": {"ms_per_step": round(ms_per_step, 4), "sclk_under_load": sclk(state_r),
                                    "kernel_ms": [round(float(v), 4) for v in kms]},
                  "constant_inputs": {"ms_per_step": round(float(c0.elapsed_time(c1) / args.steps), 4),
                                      "sclk_under_load": sclk(state_c), "kernel_ms": [round(float(v), 4) for v in ckms]}}
@@ -680,8 +680,8 @@ def backward_main(args, pa, wl, torch, w, x, dev, plan, out, lse):
                       f"sets (fp64, {t_cpu:.1f} s)", "seconds": round(t_cpu, 2)}
         result["parity_on_sample"] = {"dq_max_abs_over_rms": float(np.abs(dq_gpu - dq_ref).max() / rms),
                                       "dq_mean_abs_over_rms": float(np.abs(dq_gpu - dq_ref).mean() / rms)}
-    if probe:
-        result["power_probe"] = probe
+    if power:
+        result["power_probe"] = power
     emit(result)
 
 

@@ -13,8 +13,8 @@
 //   dV^T += dO^T W               (A = dO tile read TRANSPOSED from LDS, B = W packed to bf16)
 //   dK^T += Q^T dS               (A = Q tile read transposed,           B = dS packed to bf16)
 // Q and dO rows of a kv head, gathered into contiguous stacked order by the pre-pass, go
-// global -> LDS with range-checked buffer loads (2 x 16 KiB + statistics per tile), double
-// buffered, one barrier per tile.  The same two row-major tiles serve both kinds of product: read
+// global -> LDS with buffer loads (2 x 16 KiB + statistics per tile; directly for a rollout's own
+// keys, through registers for prefix keys), double buffered, one barrier per tile.  The same two row-major tiles serve both kinds of product: read
 // along the rows with 16-byte LDS reads for S and dW, and transposed with ds_read_b64_tr_b16 for
 // dV and dK (two 8-byte transposed reads build one operand); the tile's XOR swizzle is chosen so
 // that both access patterns are bank-conflict free (mfma_tiles.h).  One wavefront per SIMD (the
@@ -113,6 +113,22 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   lane_off.init(D, wave, lane, true);
   const rsrc_t r_qs = make_rsrc(qs_c), r_dos = make_rsrc(dos_c);
   const rsrc_t r_lse = make_rsrc(lse_c), r_del = make_rsrc(del_c), r_tok = make_rsrc(tok_c);
+  // Prefix key blocks: the Q and dO tiles travel global -> registers -> LDS instead of directly into the LDS.  A
+  // wavefront that runs alone on its SIMD has the 32 registers to spare, and a plain 16-byte load plus a 16-byte
+  // LDS write cost its instruction stream less than a direct-to-LDS load (-4.3 % on the pass; the causal
+  // instantiation, with its mask registers, got 4 % slower and keeps the direct loads, as do the kernels that
+  // run two wavefronts per SIMD: the log-probability GEMM lost 9 % with staged loads).
+  constexpr bool STAGED = !CAUSAL;
+  constexpr int NBLK = RowTileOffsets<D, KEY_WAVES>::BLOCKS_PER_WAVE;
+  i32x4 stage_q[NBLK], stage_do[NBLK];
+  auto stage_to_lds = [&](int buf) {
+    unsigned char* dst = smem + buf * STAGE;
+#pragma unroll
+    for (int n = 0; n < NBLK; ++n) {
+      *reinterpret_cast<i32x4*>(dst + (wave * NBLK + n) * 1024 + lane * 16) = stage_q[n];
+      *reinterpret_cast<i32x4*>(dst + G::ROW_TILE_BYTES + (wave * NBLK + n) * 1024 + lane * 16) = stage_do[n];
+    }
+  };
   auto issue_piece = [&](int tile, int buf, int piece) {
     unsigned char* dst = smem + buf * STAGE;
     const unsigned b0 = (unsigned)tile * (TILE * D * 2);  // byte offset of the tile in each of the four arrays
@@ -124,9 +140,19 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
         load_dword_to_lds(r_del, st + TILE * 4, lane * 4, m4);
         if (CAUSAL) load_dword_to_lds(r_tok, st + 2 * TILE * 4, lane * 4, m4);
       }
-      issue_full_row_tile<D, KEY_WAVES>(dst, r_qs, b0, lane_off, wave);
+      if (STAGED) {
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) stage_q[n] = load_chunk(r_qs, lane_off.off[n], b0);
+      } else {
+        issue_full_row_tile<D, KEY_WAVES>(dst, r_qs, b0, lane_off, wave);
+      }
     } else if (piece == 1) {
-      issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, r_dos, b0, lane_off, wave);
+      if (STAGED) {
+#pragma unroll
+        for (int n = 0; n < NBLK; ++n) stage_do[n] = load_chunk(r_dos, lane_off.off[n], b0);
+      } else {
+        issue_full_row_tile<D, KEY_WAVES>(dst + G::ROW_TILE_BYTES, r_dos, b0, lane_off, wave);
+      }
     }
   };
 
@@ -155,7 +181,8 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   // plus an immediate (no address arithmetic in the step stream).
   auto tile_body = [&](int tile, auto buf_c) {
     constexpr int buf = decltype(buf_c)::value;
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): direct-to-LDS loads of this wavefront have landed
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's loads of the tile have landed (LDS or registers)
+    if (STAGED) stage_to_lds(buf);        // staged tile -> LDS; buffer `buf` was last read two tiles ago
     __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
     // the tile after the last one is the last one again: a harmless reload into the idle buffer,
     // which keeps the step stream free of branches

@@ -212,6 +212,10 @@ __device__ inline void load_dword_to_lds(rsrc_t r, unsigned char* dst, unsigned 
 __device__ inline void load_chunk_to_lds(rsrc_t r, unsigned char* dst, unsigned lane_byte_offset, unsigned byte_offset) {
   __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (PA_LDS_PTR(void))dst, 16, lane_byte_offset, byte_offset, 0, 0);
 }
+// 16 bytes per lane into registers (same addressing)
+__device__ inline i32x4 load_chunk(rsrc_t r, unsigned lane_byte_offset, unsigned byte_offset) {
+  return __builtin_bit_cast(i32x4, __builtin_amdgcn_raw_buffer_load_b128(r, lane_byte_offset, byte_offset, 0));
+}
 #else
 // The host pass of hipcc still parses kernel bodies but has no buffer-resource type: empty stand-ins.
 struct rsrc_t {};
@@ -222,6 +226,7 @@ template <int BYTES, int NW>
 __device__ inline void issue_linear(unsigned char*, rsrc_t, unsigned, int, int) {}
 __device__ inline void load_dword_to_lds(rsrc_t, unsigned char*, unsigned, unsigned) {}
 __device__ inline void load_chunk_to_lds(rsrc_t, unsigned char*, unsigned, unsigned) {}
+__device__ inline i32x4 load_chunk(rsrc_t, unsigned, unsigned) { return i32x4{0, 0, 0, 0}; }
 #endif
 
 // Pack four fp32 accumulator registers [r0, r0+4) of a 16-register block into the B operand
