@@ -53,7 +53,7 @@ def test_c4_hour_long_sampled_rows():
 
 
 def test_c5_max_frames_ragged_sampled_rows():
-    x, out, lse = sampled_parity("C5", n_random=1, stride=2048, item_bounds=1)
+    x, out, lse = sampled_parity("C5", n_random=1, stride=4096, item_bounds=1)
     assert len(set(x.suffix_lens.tolist())) > 8   # really ragged
 
 
@@ -123,7 +123,8 @@ def test_c5_backward_ragged_sampled_dq_rows_and_value_identity():
     got = run_hip_backward(x, do, bits)
     for n, a in got.items():
         assert np.isfinite(a).all(), n
-    rows = wl.sample_rows(x.suffix_lens, w.prompt_len, 1 << 20, 1, seed=13)      # first/last/prompt boundary + 1 random per rollout
+    # first/last/prompt boundary + 1 random per rollout; every other one of them (a row costs the oracle 1.1e10 FLOP)
+    rows = wl.sample_rows(x.suffix_lens, w.prompt_len, 1 << 20, 1, seed=13)[::2]
     dq_ref, _ = cref.prefix_shared_attention_backward(x.q, x.k_prefix, x.v_prefix, x.k_suffix, x.v_suffix,
                                                       x.suffix_lens, w.scale, do, rows=rows)
     check_grad_tensor(got["dq"][rows], dq_ref, "bf16", f"C5 backward dq on {len(rows)} rows")
