@@ -267,13 +267,21 @@ int64_t prefix_attn_plan_num_items(const prefix_attn_plan_t* plan, int32_t pass)
  * dQ pass with key0 = 0 and pkeys = P, laid out over the XCDs like the prefix pass. */
 int prefix_attn_plan_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
 
-/* Work list of the backward dK/dV pass (0 = prefix key blocks, 1 = suffix key blocks), padding
- * entries included; items_out [num_items][6] (HOST): {rollout g (-1 for prefix keys), first key
- * of the block, kv head c (-1 = padding entry), number of keys in the block, and for prefix
- * blocks the range [tile0, tile1) of 64-row tiles of the kv head's stacked query rows that the
- * item streams (a short prefix is split over several items per key block)}. */
+/* Work lists of the backward dK/dV pass, padding entries included.  pass 0 = prefix key blocks, 1 = the
+ * rollouts' own key blocks (masked kernel), 2 = the rollouts' own key blocks once more for the mask-free
+ * kernel (empty unless the plan splits that pass: long rollouts, bf16).  items_out [num_items][6] (HOST):
+ * {rollout g (-1 in passes 0 and 2), first key of the block (pass 0: prefix index; pass 1: position inside the
+ *  rollout; pass 2: packed token index), kv head c (-1 = padding entry), number of keys in the block, and the
+ *  range [tile0, tile1) of 64-row tiles of the kv head's stacked query rows that the item streams}.
+ * Pass 0: a short prefix is split over several items per key block.  Passes 1 and 2 of a split plan: a block's
+ * masked item streams the tiles that hold rows needing the causal mask (its diagonal) plus, via
+ * prefix_attn_plan_key_item_extra_tiles, the rollout's last tile when rows of the next rollout share it; its
+ * mask-free item streams the tiles between; together they cover every tile from the block's first key to the
+ * rollout's end exactly once. */
 int64_t prefix_attn_plan_num_key_items(const prefix_attn_plan_t* plan, int32_t pass);
 int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out);
+/* tiles_out [num_items] (HOST): for pass 1 the one row tile an item streams after [tile0, tile1), or -1. */
+int prefix_attn_plan_key_item_extra_tiles(const prefix_attn_plan_t* plan, int32_t pass, int32_t* tiles_out);
 
 /* Total suffix tokens T of the plan. */
 int64_t prefix_attn_plan_total_tokens(const prefix_attn_plan_t* plan);

@@ -25,7 +25,7 @@ EXPORTED_SYMBOLS = ("prefix_attn_plan", "prefix_attn_forward", "prefix_attn_forw
                     "prefix_attn_status_string", "prefix_attn_plan_tiles", "prefix_attn_plan_num_items",
                     "prefix_attn_plan_items", "prefix_attn_plan_total_tokens", "prefix_attn_backward_workspace",
                     "prefix_attn_backward", "prefix_attn_backward_timed", "prefix_attn_plan_num_key_items",
-                    "prefix_attn_plan_key_items", "prefix_attn_forward_partial", "prefix_attn_merge_partials")
+                    "prefix_attn_plan_key_items", "prefix_attn_plan_key_item_extra_tiles", "prefix_attn_forward_partial", "prefix_attn_merge_partials")
 EXPORTED_SYMBOLS_OTHER = ("token_logprob_workspace", "token_logprob_forward", "grpo_group_advantages")
 
 
@@ -104,6 +104,8 @@ def load_library():
     lib.prefix_attn_plan_num_key_items.argtypes = [vp, ctypes.c_int32]
     lib.prefix_attn_plan_key_items.restype = ctypes.c_int
     lib.prefix_attn_plan_key_items.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
+    lib.prefix_attn_plan_key_item_extra_tiles.restype = ctypes.c_int
+    lib.prefix_attn_plan_key_item_extra_tiles.argtypes = [vp, ctypes.c_int32, ctypes.POINTER(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -159,9 +161,23 @@ class PrefixAttnPlan:
             raise PrefixAttnError(st, "prefix_attn_backward_workspace")
         return int(n.value)
 
+    def key_item_extra_tiles(self, which: int) -> np.ndarray:
+        """int32 [n]: the one row tile an item of dK/dV list `which` streams after [tile0, tile1), or -1."""
+        lib = load_library()
+        n = lib.prefix_attn_plan_num_key_items(self.handle, which)
+        if n < 0:
+            raise PrefixAttnError(2, "prefix_attn_plan_num_key_items")
+        out = np.full(n, -1, dtype=np.int32)
+        if n:
+            st = lib.prefix_attn_plan_key_item_extra_tiles(self.handle, which, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)))
+            if st:
+                raise PrefixAttnError(st, "prefix_attn_plan_key_item_extra_tiles")
+        return out
+
     def key_items(self, which: int) -> np.ndarray:
-        """dK/dV work list, 0 (prefix key blocks) or 1 (suffix key blocks): int32 [n, 6] =
-        (g, key0, c, nkeys, tile0, tile1); [tile0, tile1) is the row-tile range of a prefix item."""
+        """dK/dV work list, 0 (prefix key blocks), 1 (the rollouts' own key blocks, masked kernel) or 2 (the same
+        blocks for the mask-free kernel, empty unless the plan splits that pass): int32 [n, 6] =
+        (g, key0, c, nkeys, tile0, tile1); [tile0, tile1) is the range of row tiles the item streams."""
         lib = load_library()
         n = lib.prefix_attn_plan_num_key_items(self.handle, which)
         if n < 0:

@@ -66,14 +66,18 @@ struct BwdDkvArgs {
   const int32_t* toks;
   void* dk;             // same shape as k
   void* dv;
-  float* partial;       // prefix keys with row_splits > 1: fp32 partial gradients [2][row_splits][P][Hkv][D]
+  float* partial;       // partials == true: unscaled fp32 partial gradients [2][splits][P][Hkv][D]
   const KeyItem* items;
   const int32_t* cu;
-  int64_t num_items, T, Mpad, P;
-  int32_t row_splits;
+  int64_t num_items, T, Mpad;
+  int64_t P;            // keys (rows) of k / v / dk / dv: the prefix length, or T for the rollouts' own keys
+  int32_t splits;       // partial-gradient slots (an item writes slot KeyItem::split)
   int32_t Hkv, D, group;
   float scale;
-  bool causal;          // false: prefix keys; true: a rollout's own keys
+  bool causal;          // true: the masked kernel (keys indexed inside their rollout, rows from the key on);
+                        // false: the mask-free kernel (keys indexed over the whole array, every streamed row sees them)
+  bool partials;        // items leave fp32 partials instead of writing dk / dv
+  bool reduce;          // after the launch, add the slots of `partial` into dk / dv (scaled, in the tensors' dtype)
 };
 int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream);
 

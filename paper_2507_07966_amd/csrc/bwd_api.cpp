@@ -170,27 +170,41 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
   kv.group = plan->group;
   kv.scale = d.softmax_scale;
   kv.partial = reinterpret_cast<float*>(ws + plan->boff_part);
-  kv.P = d.prefix_len;
-  kv.row_splits = plan->row_splits;
   if (has_prefix) {
     kv.k = x.k_prefix;
     kv.v = x.v_prefix;
     kv.dk = x.dk_prefix;
     kv.dv = x.dv_prefix;
+    kv.P = d.prefix_len;
     kv.items = plan->d_key_items[0];
     kv.num_items = (int64_t)plan->key_items[0].size();
     kv.causal = false;
+    kv.partials = kv.reduce = plan->row_splits > 1;
+    kv.splits = plan->row_splits;
     if (pa::launch_bwd_dkv_bf16(kv, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
+  // the rollouts' own keys: the masked kernel (on the tiles that need the mask only, when the plan splits the
+  // pass), then the mask-free kernel on the other tiles and the sum of the two partial gradients
   kv.k = x.k_suffix;
   kv.v = x.v_suffix;
   kv.dk = x.dk_suffix;
   kv.dv = x.dv_suffix;
+  kv.P = plan->T;
   kv.items = plan->d_key_items[1];
   kv.num_items = (int64_t)plan->key_items[1].size();
   kv.causal = true;
+  kv.partials = plan->suffix_split;
+  kv.reduce = false;
+  kv.splits = 2;
   if (pa::launch_bwd_dkv_bf16(kv, hip_stream) != 0) return PA_ERR_HIP;
+  if (plan->suffix_split) {
+    kv.items = plan->d_key_items_full;
+    kv.num_items = (int64_t)plan->key_items_full.size();
+    kv.causal = false;
+    kv.reduce = true;
+    if (pa::launch_bwd_dkv_bf16(kv, hip_stream) != 0) return PA_ERR_HIP;
+  }
   if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
   return PA_OK;
 }

@@ -36,9 +36,12 @@ using namespace mt;
 constexpr int KV_THREADS = KEY_WAVES * 64;
 constexpr float LOG2E = 1.4426950408889634f;
 
-// PARTIAL (prefix keys of a short prefix): the item streams only the row tiles [tile0, tile1) of its
-// kv head and leaves fp32 partial gradients in `partial` ([2][splits][P][Hkv][D]); a reduction
-// kernel adds the splits.
+// PARTIAL: the item leaves unscaled fp32 partial gradients in slot `it.split` of `partial`
+// ([2][splits][P][Hkv][D], P = number of keys of the array k / v) and a reduction kernel adds the slots.  Used for
+// the prefix keys of a short prefix (each item streams one range of row tiles) and for a rollout's own keys
+// when their pass is split: the CAUSAL instantiation then streams only the tiles that need the mask (the
+// block's diagonal, and the rollout's last tile if rows of the next rollout share it), the mask-free
+// instantiation the tiles between, with the keys indexed over all packed tokens (P = T).
 template <int D, bool CAUSAL, bool PARTIAL>
 __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     const __bf16* __restrict__ k, const __bf16* __restrict__ v, const __bf16* __restrict__ qs,
@@ -48,7 +51,6 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     __bf16* __restrict__ dv, float* __restrict__ partial, int64_t P, int splits,
     const KeyItem* __restrict__ items, const int32_t* __restrict__ cu, int64_t T, int64_t Mpad, int Hkv, int group,
     float scale) {
-  static_assert(!(CAUSAL && PARTIAL), "only prefix key blocks are split");
   using G = Geo<D>;
   constexpr int KK = G::KK, DB = G::DB;
   constexpr int STATS = 1024;  // per row: LSE*log2e, delta, packed token index (3 x 64 words)
@@ -93,10 +95,15 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     for (int db = 0; db < DB; ++db) troff[half][db] = tr_operand_offset<D>(lane, db, 0, half);
 
   // ---- row tiles: stacked rows M = t * group + j of kv head c, 64 per tile, numbered over all packed tokens
-  const int64_t m_begin = CAUSAL ? (int64_t)(off_g + it.key0) * group : 0;
-  const int64_t m_end = CAUSAL ? (int64_t)end_g * group : T * group;
-  const int tile0 = CAUSAL ? (int)(m_begin / TILE) : it.tile0;
-  const int tile1 = CAUSAL ? (int)((m_end + TILE - 1) / TILE) : it.tile1;
+  // the plan names the row tiles: [tile0, tile1) and, for a masked item, possibly one more tile after them
+  const int tile0 = it.tile0, tile1 = it.tile1;
+  // A mask-free item of a rollout's own keys (g == -2) walks its tiles from the rollout's end backwards: all key
+  // blocks of a rollout share that end, so the blocks running at the same time stream the same tiles and share
+  // them in L2 (walking forwards from its own diagonal, every block would be somewhere else).
+  const int extra = CAUSAL ? it.extra_tile : -1;
+  const bool backwards = !CAUSAL && it.g == -2;
+  const int ntile = tile1 - tile0 + (extra >= 0 ? 1 : 0);
+  auto tile_at = [&](int n) { return backwards ? tile1 - 1 - n : (n < tile1 - tile0 ? tile0 + n : extra); };
   const int64_t head_rows = (int64_t)it.c * Mpad;
   const __bf16* qs_c = qs + head_rows * D;
   const __bf16* dos_c = dos + head_rows * D;
@@ -173,20 +180,20 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
   // although only one wavefront runs per SIMD.
   constexpr int NSW = 2 * KK, NDK = 4 * DB, NS = NSW + NDK, PF = 2;
 
-  if (tile0 < tile1) {
+  if (ntile > 0) {
 #pragma unroll
-    for (int piece = 0; piece < 2; ++piece) issue_piece(tile0, 0, piece);
+    for (int piece = 0; piece < 2; ++piece) issue_piece(tile_at(0), 0, piece);
   }
   // The tile body exists once per LDS buffer, so that every LDS address in it is the lane's constant offset
   // plus an immediate (no address arithmetic in the step stream).
-  auto tile_body = [&](int tile, auto buf_c) {
+  auto tile_body = [&](int n, auto buf_c) {
     constexpr int buf = decltype(buf_c)::value;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wavefront's loads of the tile have landed (LDS or registers)
     if (STAGED) stage_to_lds(buf);        // staged tile -> LDS; buffer `buf` was last read two tiles ago
     __syncthreads();                      // all shares of the tile (and wavefront 0's statistics) are visible
     // the tile after the last one is the last one again: a harmless reload into the idle buffer,
     // which keeps the step stream free of branches
-    const int next_tile = tile + 1 < tile1 ? tile + 1 : tile;
+    const int next_tile = tile_at(n + 1 < ntile ? n + 1 : n);
     const unsigned char* qt = smem + buf * STAGE;
     const unsigned char* dt = qt + G::ROW_TILE_BYTES;
     const float* st = reinterpret_cast<const float*>(qt + 2 * G::ROW_TILE_BYTES);
@@ -285,18 +292,18 @@ __global__ __launch_bounds__(KV_THREADS, 1) void bwd_dkv_kernel(
     }
   };
   {
-    int tile = tile0;
-    for (; tile + 1 < tile1; tile += 2) {
-      tile_body(tile, std::integral_constant<int, 0>{});
-      tile_body(tile + 1, std::integral_constant<int, 1>{});
+    int n = 0;
+    for (; n + 1 < ntile; n += 2) {
+      tile_body(n, std::integral_constant<int, 0>{});
+      tile_body(n + 1, std::integral_constant<int, 1>{});
     }
-    if (tile < tile1) tile_body(tile, std::integral_constant<int, 0>{});
+    if (n < ntile) tile_body(n, std::integral_constant<int, 0>{});
   }
 
   // ---- epilogue: register i of block db is channel db*32 + 8*(i/4) + 4*hf + i%4 of this lane's key
   if (PARTIAL) {
     if (key_ok) {
-      float* pk = partial + (((int64_t)it.split * P + key) * Hkv + it.c) * D + 4 * hf;
+      float* pk = partial + (((int64_t)it.split * P + off_g + key) * Hkv + it.c) * D + 4 * hf;
       float* pv = pk + (int64_t)splits * P * Hkv * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
@@ -344,27 +351,33 @@ __global__ __launch_bounds__(256) void bwd_dkv_reduce_kernel(const float* __rest
 }  // namespace
 
 int launch_bwd_dkv_bf16(const BwdDkvArgs& a, void* stream) {
-  if (a.num_items == 0) return 0;
   hipStream_t s = static_cast<hipStream_t>(stream);
   auto b = [](const void* p) { return static_cast<const __bf16*>(p); };
-  const unsigned grid = (unsigned)a.num_items;
-  const bool part = !a.causal && a.row_splits > 1;
+  if (a.num_items > 0) {
+    const unsigned grid = (unsigned)a.num_items;
 #define PA_LAUNCH(DD, CC, PP)                                                                                      \
   bwd_dkv_kernel<DD, CC, PP><<<grid, KV_THREADS, 0, s>>>(                                                          \
       b(a.k), b(a.v), b(a.qs), b(a.dos), a.lse2s, a.deltas, a.toks, static_cast<__bf16*>(a.dk),                    \
-      static_cast<__bf16*>(a.dv), a.partial, a.P, a.row_splits, a.items, a.cu, a.T, a.Mpad, a.Hkv, a.group, a.scale)
-  if (a.D == 128) {
-    if (a.causal) PA_LAUNCH(128, true, false); else if (part) PA_LAUNCH(128, false, true); else PA_LAUNCH(128, false, false);
-  } else {
-    if (a.causal) PA_LAUNCH(64, true, false); else if (part) PA_LAUNCH(64, false, true); else PA_LAUNCH(64, false, false);
-  }
+      static_cast<__bf16*>(a.dv), a.partial, a.P, a.splits, a.items, a.cu, a.T, a.Mpad, a.Hkv, a.group, a.scale)
+#define PA_LAUNCH_D(DD)                                                                                            \
+  if (a.causal && a.partials) PA_LAUNCH(DD, true, true);                                                           \
+  else if (a.causal) PA_LAUNCH(DD, true, false);                                                                   \
+  else if (a.partials) PA_LAUNCH(DD, false, true);                                                                 \
+  else PA_LAUNCH(DD, false, false)
+    if (a.D == 128) {
+      PA_LAUNCH_D(128);
+    } else {
+      PA_LAUNCH_D(64);
+    }
+#undef PA_LAUNCH_D
 #undef PA_LAUNCH
-  if (hipGetLastError() != hipSuccess) return 1;
-  if (part) {
+    if (hipGetLastError() != hipSuccess) return 1;
+  }
+  if (a.partials && a.reduce) {
     const int64_t n4 = a.P * a.Hkv * a.D / 4;
     const int64_t want = (n4 + 255) / 256;
     bwd_dkv_reduce_kernel<<<(unsigned)(want < 8192 ? want : 8192), 256, 0, s>>>(
-        a.partial, static_cast<__bf16*>(a.dk), static_cast<__bf16*>(a.dv), n4, a.row_splits, a.scale);
+        a.partial, static_cast<__bf16*>(a.dk), static_cast<__bf16*>(a.dv), n4, a.splits, a.scale);
   }
   return (int)hipGetLastError();
 }

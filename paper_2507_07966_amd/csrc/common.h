@@ -51,10 +51,10 @@ struct KeyItem {
   int32_t key0;   // first key of the block (prefix index, or position inside the rollout)
   int32_t c;      // kv head
   int32_t nkeys;  // keys in the block (<= KEYS_PER_KEY_ITEM)
-  int32_t tile0;  // prefix blocks: the row tiles [tile0, tile1) of the kv head this item streams
-  int32_t tile1;  //   (a short prefix is split over `row_splits` items per key block to fill the chip)
-  int32_t split;  // prefix blocks: which of the row splits this is
-  int32_t pad_;
+  int32_t tile0;  // the row tiles [tile0, tile1) of the kv head this item streams (a short prefix is split over
+  int32_t tile1;  //   `row_splits` items per key block to fill the chip; a rollout's own keys: see suffix_split)
+  int32_t split;  // which partial-gradient slot the item writes when its pass leaves partials
+  int32_t extra_tile;  // masked suffix items: one more row tile after [tile0, tile1), or -1
 };
 
 // Arguments of one attention pass (prefix or suffix).  All pointers are device pointers.
@@ -166,6 +166,12 @@ struct prefix_attn_plan {
   pa::KeyItem* d_key_items[2] = {nullptr, nullptr};
   int64_t Mpad = 0;                    // stacked rows per kv head, rounded up to ROWS_PER_ROW_TILE
   int32_t row_splits = 1;              // items per prefix key block (> 1: fp32 partial gradients are reduced)
+  // A rollout's own key block sees masked rows only near its diagonal and in the rollout's last, partly filled
+  // row tile.  With suffix_split the masked kernel streams just those tiles (key_items[1]) and the mask-free
+  // kernel the rest (key_items_full); both leave fp32 partials that a reduction adds.
+  bool suffix_split = false;
+  std::vector<pa::KeyItem> key_items_full;
+  pa::KeyItem* d_key_items_full = nullptr;
   size_t boff_delta = 0, boff_lse_th = 0, boff_qs = 0, boff_dos = 0, boff_lse2s = 0, boff_deltas = 0,
          boff_toks = 0, boff_ktp = 0, boff_kts = 0, boff_part = 0, boff_dqpart = 0, bws_bytes = 0;
 };

@@ -210,16 +210,60 @@ void build_key_items(prefix_attn_plan_t& p) {
         }
     interleave_over_xcds(per_head, p.num_xcd, pa::KeyItem{-1, 0, -1, 0, 0, 0, 0, 0}, pre);
   }
+  // A rollout's own key blocks.  Row r (position i) sees key j of its rollout iff i >= j, so a block of keys
+  // [key0, key0 + n) needs the mask only on the rows at positions key0 .. key0 + n - 2 (the diagonal) and in
+  // the rollout's last row tile when that tile also holds rows of the next rollout; every tile between is
+  // fully visible.  Long rollouts (bf16) therefore run as two items per block: the masked kernel on the
+  // diagonal tiles plus that last tile, the mask-free kernel on the tiles between, each leaving fp32 partial
+  // gradients that a reduction adds.  The mask-free items walk their tiles from the rollout's end backwards:
+  // all blocks of a rollout share that end, so the blocks running at the same time stream the same Q/dO tiles
+  // and share them in L2, where the masked kernel, which starts every block at its own diagonal, fetched
+  // 40 GB per launch for a 32,768-token sequence.  Short rollouts keep one masked item per block.
   std::vector<pa::KeyItem>& suf = p.key_items[1];
+  std::vector<pa::KeyItem>& full = p.key_items_full;
   suf.clear();
+  full.clear();
+  const int RT = pa::ROWS_PER_ROW_TILE;
+  struct Ranges { int32_t tile_b, tile_full, tile_e_full, tile_e; };
+  auto ranges = [&](int g, int key0, int n) {
+    const int64_t m_begin = (int64_t)(p.cu[g] + key0) * p.group;
+    const int64_t m_full = (int64_t)(p.cu[g] + key0 + n - 1) * p.group;  // first row that sees the whole block
+    const int64_t m_end = (int64_t)p.cu[g + 1] * p.group;
+    return Ranges{(int32_t)(m_begin / RT), (int32_t)((m_full + RT - 1) / RT), (int32_t)(m_end / RT),
+                  (int32_t)((m_end + RT - 1) / RT)};
+  };
+  // Worth it for long rollouts only (measured: a 32,768-token sequence -4 ... -9 % on the pass depending on the
+  // box, a 230,400-token one -6.7 %, 2,304-token rollouts +8 %: two launches, partials and a reduction for little
+  // mask-free work).
+  constexpr int SPLIT_MIN_TILES = 512;
+  p.suffix_split = false;
+  if (p.desc.dtype == PA_BF16)
+    for (int g = 0; g < p.desc.num_rollouts && !p.suffix_split; ++g) {
+      const Ranges r = ranges(g, 0, std::min(KB, p.lens[g]));
+      p.suffix_split = r.tile_e_full - r.tile_full >= SPLIT_MIN_TILES;  // a rollout's first block has the longest mask-free range
+    }
   for (int c = 0; c < Hkv; ++c)
     for (int g = 0; g < p.desc.num_rollouts; ++g)
-      for (int key0 = 0; key0 < p.lens[g]; key0 += KB)
-        suf.push_back({g, key0, c, std::min(KB, p.lens[g] - key0), 0, 0, 0, 0});
-  const std::vector<int32_t>& lens = p.lens;
-  std::stable_sort(suf.begin(), suf.end(), [&lens](const pa::KeyItem& a, const pa::KeyItem& b) {
-    return lens[a.g] - a.key0 > lens[b.g] - b.key0;
-  });
+      for (int key0 = 0; key0 < p.lens[g]; key0 += KB) {
+        const int n = std::min(KB, p.lens[g] - key0);
+        const Ranges r = ranges(g, key0, n);
+        if (p.suffix_split && r.tile_e_full > r.tile_full) {
+          suf.push_back({g, key0, c, n, r.tile_b, r.tile_full, 0, r.tile_e_full < r.tile_e ? r.tile_e_full : -1});
+          // the mask-free kernel indexes keys over all packed tokens: key0 is the packed token index here
+          full.push_back({-2, p.cu[g] + key0, c, n, r.tile_full, r.tile_e_full, 1, -1});
+        } else {
+          suf.push_back({g, key0, c, n, r.tile_b, r.tile_e, 0, -1});
+          if (p.suffix_split) full.push_back({-1, p.cu[g] + key0, c, n, 0, 0, 1, -1});  // no tiles: writes zeros
+        }
+      }
+  auto tiles_of = [](const pa::KeyItem& a) { return a.tile1 - a.tile0 + (a.extra_tile >= 0 ? 1 : 0); };
+  std::stable_sort(suf.begin(), suf.end(), [&](const pa::KeyItem& a, const pa::KeyItem& b) { return tiles_of(a) > tiles_of(b); });
+  std::stable_sort(full.begin(), full.end(), [&](const pa::KeyItem& a, const pa::KeyItem& b) { return tiles_of(a) > tiles_of(b); });
+  if (!full.empty()) {  // one kv head per subset of XCDs, longest first inside a head (-1.3 % on the pass)
+    std::vector<std::vector<pa::KeyItem>> per_head(Hkv);
+    for (const pa::KeyItem& it : full) per_head[it.c].push_back(it);
+    interleave_over_xcds(per_head, p.num_xcd, pa::KeyItem{-1, 0, -1, 0, 0, 0, 0, -1}, full);
+  }
 }
 
 // Backward workspace: delta and the re-ordered LSE (used by the fp32 path); for bf16 also the stacked Q/dO copies, the
@@ -243,9 +287,14 @@ void layout_backward_workspace(prefix_attn_plan_t& p) {
     p.boff_ktp = p.boff_toks + stats;
     p.boff_kts = p.boff_ktp + align_up((size_t)d.num_kv_heads * p.tiles_prefix * image, 256);
     end = p.boff_kts + align_up((size_t)d.num_kv_heads * p.tiles_suffix * image, 256);
-    p.boff_part = end;  // fp32 partial dK, dV of the prefix per row split: [2][row_splits][P][Hkv][D]
-    if (p.row_splits > 1)
-      end += align_up((size_t)2 * p.row_splits * d.prefix_len * d.num_kv_heads * d.head_dim * sizeof(float), 256);
+    // fp32 partial dK, dV: of the prefix per row split [2][row_splits][P][Hkv][D]; of the rollouts' own keys, when
+    // their pass is split into a masked and a mask-free item per block, [2][2][T][Hkv][D].  The two stages run
+    // one after the other and share the region.
+    p.boff_part = end;
+    size_t part = 0;
+    if (p.row_splits > 1) part = (size_t)2 * p.row_splits * d.prefix_len * d.num_kv_heads * d.head_dim * sizeof(float);
+    if (p.suffix_split) part = std::max(part, (size_t)2 * 2 * p.T * d.num_kv_heads * d.head_dim * sizeof(float));
+    end += align_up(part, 256);
     p.boff_dqpart = end;  // fp32 partial dQ per key split: [key_splits][T][Hq][D]
     if (p.key_splits > 1) end += align_up((size_t)p.key_splits * rows * d.head_dim * sizeof(float), 256);
   }
@@ -352,6 +401,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
       // so that the call itself only reads a table
       void* unused = nullptr;
       ok = ok && pa::static_scratch(desc->device, &unused) == PA_OK;
+      if (ok && !p->key_items_full.empty()) {
+        const size_t bytes = p->key_items_full.size() * sizeof(pa::KeyItem);
+        ok = hipMalloc((void**)&p->d_key_items_full, bytes) == hipSuccess &&
+             hipMemcpy(p->d_key_items_full, p->key_items_full.data(), bytes, hipMemcpyHostToDevice) == hipSuccess;
+      }
       (void)hipSetDevice(prev);
     }
     if (!ok) {
@@ -372,6 +426,7 @@ void prefix_attn_destroy(prefix_attn_plan_t* plan) {
     if (plan->d_items[s]) (void)hipFree(plan->d_items[s]);
   for (int s = 0; s < 2; ++s)
     if (plan->d_key_items[s]) (void)hipFree(plan->d_key_items[s]);
+  if (plan->d_key_items_full) (void)hipFree(plan->d_key_items_full);
   if (plan->d_dq_items) (void)hipFree(plan->d_dq_items);
   if (plan->d_sweep_items) (void)hipFree(plan->d_sweep_items);
   delete plan;
@@ -427,14 +482,14 @@ int prefix_attn_backward_workspace(const prefix_attn_plan_t* plan, size_t* works
 }
 
 int64_t prefix_attn_plan_num_key_items(const prefix_attn_plan_t* plan, int32_t pass) {
-  if (!plan || pass < 0 || pass > 1) return -1;
-  return (int64_t)plan->key_items[pass].size();
+  if (!plan || pass < 0 || pass > 2) return -1;
+  return (int64_t)(pass == 2 ? plan->key_items_full : plan->key_items[pass]).size();
 }
 
 int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int32_t* items_out) {
   if (!plan || !items_out) return PA_ERR_NULL;
-  if (pass < 0 || pass > 1) return PA_ERR_SHAPE;
-  const std::vector<pa::KeyItem>& v = plan->key_items[pass];
+  if (pass < 0 || pass > 2) return PA_ERR_SHAPE;
+  const std::vector<pa::KeyItem>& v = pass == 2 ? plan->key_items_full : plan->key_items[pass];
   for (size_t n = 0; n < v.size(); ++n) {
     items_out[6 * n + 0] = v[n].g;
     items_out[6 * n + 1] = v[n].key0;
@@ -443,6 +498,14 @@ int prefix_attn_plan_key_items(const prefix_attn_plan_t* plan, int32_t pass, int
     items_out[6 * n + 4] = v[n].tile0;
     items_out[6 * n + 5] = v[n].tile1;
   }
+  return PA_OK;
+}
+
+int prefix_attn_plan_key_item_extra_tiles(const prefix_attn_plan_t* plan, int32_t pass, int32_t* tiles_out) {
+  if (!plan || !tiles_out) return PA_ERR_NULL;
+  if (pass < 0 || pass > 2) return PA_ERR_SHAPE;
+  const std::vector<pa::KeyItem>& v = pass == 2 ? plan->key_items_full : plan->key_items[pass];
+  for (size_t n = 0; n < v.size(); ++n) tiles_out[n] = pass == 1 ? v[n].extra_tile : -1;
   return PA_OK;
 }
 

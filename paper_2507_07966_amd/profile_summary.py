@@ -32,10 +32,12 @@ def short_name(k: str) -> str:
         return "bwd_dkv_prefix: add row splits"
     if "bwd_dq_reduce" in k:
         return "bwd_dq: add key splits"
-    if "bwd_dkv_kernel" in k:
+    if "bwd_dkv_kernel" in k:      # <head_dim, masked, partial gradients>
         if "ELb1ELb0E" in k:
             return "bwd_dkv_suffix (bf16 MFMA)"
-        return "bwd_dkv_prefix (bf16 MFMA)" + (", row splits" if "ELb0ELb1E" in k else "")
+        if "ELb1ELb1E" in k:
+            return "bwd_dkv_suffix (bf16 MFMA), masked tiles, partials"
+        return "bwd_dkv mask-free (bf16 MFMA)" + (", partials" if "ELb0ELb1E" in k else ", prefix keys")
     if "bwd_dq_kernel" in k:
         return "bwd_dq (bf16 MFMA)" + (", key splits" if "ELb1E" in k else "")
     if "bwd_prep" in k:

@@ -96,6 +96,24 @@ def test_backward_direct_key_block_path_full_tensor():
     check_grads(got, oracle_backward(x, do), "bf16", "direct dK/dV path, 16K prefix")
 
 
+@pytest.mark.parametrize("D", [128, 64])
+def test_backward_long_rollouts_masked_and_mask_free_items_full_tensor(D):
+    """Rollouts long enough (512 row tiles and more) that the dK/dV pass over their own keys is split: per key
+    block a masked item on the diagonal tiles (plus the rollout's last tile, which here also holds rows of the
+    next rollout) and a mask-free item that walks the tiles between backwards, two fp32 partial gradients and
+    their sum.  Element by element against the oracle; one kv head keeps the oracle at a few 1e11 FLOP."""
+    import paper_2507_07966_amd as pa
+    shape = (7, 1, D, 64, (5000, 33, 5300))
+    plan = pa.prefix_attn_plan(*shape[:4], list(shape[4]), D ** -0.5, dtype="bf16", device=-1)
+    free = plan.key_items(2)
+    assert (free[:, 0] == -2).sum() >= 60 and (plan.key_item_extra_tiles(1) >= 0).sum() >= 30
+    plan.destroy()
+    x = wl.make_custom("bf16", *shape, seed=29)
+    do, bits = wl.make_d_out(x)
+    got = run_hip_backward(x, do, bits)
+    check_grads(got, oracle_backward(x, do), "bf16", f"long rollouts, split dK/dV pass, D={D}")
+
+
 def test_backward_and_logprob_on_side_stream_and_graph_replay():
     """Neither call allocates or synchronises, so both can run on any stream and be captured into a HIP graph;
     every replay must reproduce the eager result bit for bit (stale workspace contents must not matter)."""

@@ -235,14 +235,63 @@ def key_coverage(plan, Hq, Hkv, P, lens):
         assert (pre[c] == 1).all()
         for g in range(len(lens)):
             assert (suf[c][g] == 1).all()
+    suffix_tile_coverage(plan, Hq // Hkv, Hkv, lens)
+
+
+def suffix_tile_coverage(plan, group, Hkv, lens):
+    """The rollouts' own key blocks: the tiles of the masked item (its range and its extra tile) and of the
+    mask-free item (when the plan splits the pass) together are exactly the row tiles from the block's first key
+    to the rollout's end, each once; every row of a mask-free tile lies in the block's rollout and sees all of
+    the block's keys."""
+    off = np.concatenate([[0], np.cumsum(lens)])
+    masked, extra, free = plan.key_items(1), plan.key_item_extra_tiles(1), plan.key_items(2)
+    split = len(free) > 0
+    assert not split or (free[:, 2] >= 0).sum() == len(masked)
+    seen = {}
+    for (g, key0, c, n, t0, t1), x in zip(masked.tolist(), extra.tolist()):
+        tiles = list(range(t0, t1)) + ([x] if x >= 0 else [])
+        assert len(set(tiles)) == len(tiles)
+        seen[(c, int(off[g]) + key0)] = tiles
+    for g_, pkey0, c, n, t0, t1 in free.tolist():
+        if c < 0:
+            continue
+        assert g_ in (-1, -2)
+        g = int(np.searchsorted(off, pkey0, side="right") - 1)
+        key0 = pkey0 - int(off[g])
+        for t in range(t0, t1):
+            rows = np.arange(64 * t, 64 * t + 64)                       # stacked rows M = token * group + head
+            tok = rows // group
+            assert (tok >= off[g] + key0 + n - 1).all() and (tok < off[g + 1]).all()
+        assert not set(range(t0, t1)) & set(seen[(c, pkey0)])
+        seen[(c, pkey0)] += list(range(t0, t1))
+    for (g, key0, c, n, _, _) in masked.tolist():
+        first = (int(off[g]) + key0) * group // 64
+        last = -(-int(off[g + 1]) * group // 64)
+        assert sorted(seen[(c, int(off[g]) + key0)]) == list(range(first, last)), (g, key0, c)
 
 
 @pytest.mark.parametrize("Hq,Hkv,P,lens", [
     (28, 4, 4096, [1152] * 8), (28, 4, 100, [1, 37, 300, 5]), (4, 4, 0, [70, 3]), (6, 3, 1000, [257, 256, 255]),
+    (2, 2, 129, [513]), (8, 2, 300, [1500, 700, 1]), (28, 4, 0, [4700, 33]), (7, 1, 64, [130, 127, 5000, 129]),
+    (4, 1, 7, [9000, 8300, 1]),
 ])
 def test_backward_schedule_covers_every_key_once(Hq, Hkv, P, lens):
     plan = host_plan(num_q_heads=Hq, num_kv_heads=Hkv, prefix_len=P, suffix_lens=lens)
     key_coverage(plan, Hq, Hkv, P, lens)
+
+
+def test_long_rollouts_split_their_own_key_blocks_into_masked_and_mask_free_items():
+    plan = host_plan(prefix_len=0, suffix_lens=[8192, 100])        # 896 row tiles in the long sequence: split
+    masked, free = plan.key_items(1), plan.key_items(2)
+    real = free[free[:, 2] >= 0]
+    assert len(real) == len(masked) == 4 * (64 + 1)
+    assert (masked[:, 5] - masked[:, 4]).max() <= 16               # 127 positions x 7 heads = 14 tiles of diagonal (+ edges)
+    assert (real[:, 5] - real[:, 4]).max() == 896 - 14             # the first block of the sequence: all tiles after its diagonal
+    assert (real[:, 0] == -2).sum() == 4 * 63                      # these walk backwards; the rest stream no tile
+    assert len(host_plan().key_items(2)) == 0                      # rollouts of 1,152 tokens keep one masked item per block
+    f32 = host_plan(prefix_len=0, suffix_lens=[8192], dtype="f32")
+    assert len(f32.key_items(2)) == 0
+    assert plan.backward_workspace_bytes >= 2 * 2 * 8292 * 4 * 128 * 4      # holds the two partial-gradient slots [2][2][T][Hkv][D]
 
 
 def test_backward_items_are_grouped_by_kv_head_per_xcd():
@@ -252,8 +301,8 @@ def test_backward_items_are_grouped_by_kv_head_per_xcd():
         heads = {int(it[2]) for it in items[x::8] if it[2] >= 0}
         assert len(heads) == 1
     k1 = plan.key_items(1)
-    work = np.asarray(plan.suffix_lens)[k1[:, 0]] - k1[:, 1]
-    assert (np.diff(work) <= 0).all()          # suffix key blocks: longest row range first
+    work = k1[:, 5] - k1[:, 4] + (plan.key_item_extra_tiles(1) >= 0)
+    assert (np.diff(work) <= 0).all()          # suffix key blocks: most row tiles first
 
 
 def test_backward_workspace_and_argument_checks():
@@ -265,7 +314,7 @@ def test_backward_workspace_and_argument_checks():
     images = Hkv * (P // 64 + 8 * (1152 // 64)) * D * 64 * 2
     splits = len([1 for it in plan.key_items(0) if it[2] == 0 and it[1] == 0])     # items of one key block
     assert splits == 2                                                              # 128 key blocks -> 256 items, one round
-    partials = 2 * splits * P * Hkv * D * 4
+    partials = 2 * splits * P * Hkv * D * 4            # (rollouts this short keep one masked item per own key block)
     need = 2 * T * Hq * 4 + stacked + 3 * Hkv * mpad * 4 + images + partials
     assert need <= plan.backward_workspace_bytes <= need + 12 * 256
     c3 = host_plan(prefix_len=32768, suffix_lens=[2304] * 8)
