@@ -29,7 +29,7 @@ def short_name(k: str) -> str:
             return "attention_sweep (bf16 MFMA)"
         return "suffix_pass (bf16 MFMA)" + ("" if epi == 0 else ", final" if epi == 1 else ", merging")
     if "bwd_dkv_reduce" in k:
-        return "bwd_dkv_prefix: add row splits"
+        return "bwd_dkv: add partial gradients"
     if "bwd_dq_reduce" in k:
         return "bwd_dq: add key splits"
     if "bwd_dkv_kernel" in k:      # <head_dim, masked, partial gradients>
