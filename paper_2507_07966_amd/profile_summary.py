@@ -37,7 +37,8 @@ def short_name(k: str) -> str:
             return "bwd_dkv_suffix (bf16 MFMA)"
         if "ELb1ELb1E" in k:
             return "bwd_dkv_suffix (bf16 MFMA), masked tiles, partials"
-        return "bwd_dkv mask-free (bf16 MFMA)" + (", partials" if "ELb0ELb1E" in k else ", prefix keys")
+        # mask-free: the prefix keys, or (with partial gradients) their row splits and a long rollout's own keys
+        return "bwd_dkv mask-free (bf16 MFMA), partials" if "ELb0ELb1E" in k else "bwd_dkv_prefix (bf16 MFMA)"
     if "bwd_dq_kernel" in k:
         return "bwd_dq (bf16 MFMA)" + (", key splits" if "ELb1E" in k else "")
     if "bwd_prep" in k:
