@@ -93,6 +93,7 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
   // tiles 0 .. tp-1 cover the prefix, tp .. tp+ts-1 the rollout's own keys
   const int tp = (P + TILE - 1) / TILE;
   const int ts = (nkeys + TILE - 1) / TILE;
+  const int first_pos = it.row0 / group;  // smallest causal bound among the item's rows
   const int ntiles = tp + ts;
   const __bf16* kpb = k_prefix + ((int64_t)it.key0 * Hkv + it.c) * D;
   const __bf16* vpb = v_prefix + ((int64_t)it.key0 * Hkv + it.c) * D;
@@ -148,7 +149,10 @@ __global__ __launch_bounds__(DQ_THREADS, 512 / DQ_THREADS) void bwd_dq_kernel(
     const int key_tile0 = (pre ? u : u - tp) * TILE;
     // last visible key index inside this tile's key set, for this lane's query
     const int limit = pre ? P - 1 : pos;
-    const bool no_mask = pre ? (key_tile0 + TILE <= P) : false;
+    // no masking where every key of the tile exists and is visible to every row of the item: a full prefix
+    // tile, or a tile of own keys that ends at or before the item's first position (rows past the rollout's
+    // end carry zero Q and dO, so their dS is zero either way)
+    const bool no_mask = pre ? (key_tile0 + TILE <= P) : (key_tile0 + TILE - 1 <= first_pos);
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb) {
       f32x16 S, W;
