@@ -128,9 +128,10 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     if (pa::launch_vt_images(t, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;
-  // bf16, whole call, unsplit short prefix (the plan decides): one sweep over [prefix | own keys] per block of
-  // rows does the work of the prefix pass, the suffix pass and the merge (the sweep list carries both extents)
-  const bool sweep = mode == FULL && !plan->sweep_items.empty();
+  // bf16, unsplit short prefix (the plan decides), own keys included: one sweep over [prefix | own keys] per
+  // block of rows does the work of the prefix pass, the suffix pass and the merge (the sweep list carries both
+  // extents); it leaves the result of the call, or the fp32 partial of a shard that also holds the own keys
+  const bool sweep = with_suffix && !plan->sweep_items.empty();
   if (has_prefix && !sweep) {
     a.k = k_prefix;
     a.v = v_prefix;
@@ -169,19 +170,23 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     a.lse1 = lse1;
     a.out_final = out;
     a.lse_final = lse;
-    if (sweep) {
-      a.sweep_prefix = true;
-      a.k_pre = k_prefix;
-      a.vt_pre = ws + plan->off_vtp;
-      a.vt_pre_tiles_per_head = plan->tiles_prefix;
-      a.items = plan->d_sweep_items;
-      a.num_items = (int64_t)plan->sweep_items.size();
+  }
+  if (sweep) {
+    a.sweep_prefix = true;
+    a.k_pre = k_prefix;
+    a.vt_pre = ws + plan->off_vtp;
+    a.vt_pre_tiles_per_head = plan->tiles_prefix;
+    a.items = plan->d_sweep_items;
+    a.num_items = (int64_t)plan->sweep_items.size();
+    if (!fused) {  // a shard's partial: straight into the caller's buffers
+      a.o_part = static_cast<float*>(out);
+      a.lse_part = lse_partial;
     }
   }
   if (launch_pass(a, hip_stream) != 0) return PA_ERR_HIP;
 
   if (ev && hipEventRecord(ev[3], hs) != hipSuccess) return PA_ERR_HIP;
-  if (fused) {
+  if (fused || sweep) {
     if (ev && hipEventRecord(ev[4], hs) != hipSuccess) return PA_ERR_HIP;
     return PA_OK;
   }

@@ -96,8 +96,9 @@ __device__ inline float pair_sum(float x) {
 
 // EPI (suffix pass only): 0 = leave an fp32 partial; 1 = the partial is the result (no prefix): write it
 // in bf16 with its LSE; 2 = combine with the prefix partial (o1, lse1) by log-sum-exp and write the result.
-// SWEEP (suffix pass with EPI 1 only): the item first sweeps the prefix keys [0, it.pkeys) (no mask) and then
-// the rollout's own keys, all in one online softmax, so its result is the result of the call.
+// SWEEP (suffix pass with EPI 0 or 1): the item first sweeps the prefix keys [0, it.pkeys) (no mask) and then
+// the rollout's own keys, all in one online softmax, so its result is the result of the call (EPI 1) or the
+// fp32 partial over a prefix shard and the own keys together (EPI 0).
 template <int D, bool CAUSAL, int EPI, bool SWEEP>
 __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ q, const __bf16* __restrict__ k, const __bf16* __restrict__ vt,
@@ -108,7 +109,7 @@ __global__ __launch_bounds__(NTHREADS, 512 / NTHREADS) void pass_bf16_kernel(
     const __bf16* __restrict__ k_pre, const __bf16* __restrict__ vt_pre, int64_t vt_pre_tiles_per_head,
     int64_t part_rows, int Hq, int Hkv, int group, float scale) {
   static_assert(EPI == 0 || CAUSAL, "only the suffix pass can finish the call");
-  static_assert(!SWEEP || (CAUSAL && EPI == 1), "the sweep over prefix and own keys writes the final result");
+  static_assert(!SWEEP || (CAUSAL && EPI != 2), "a sweep over prefix and own keys has nothing to combine with");
   using TL = Tile<D>;
   constexpr int KK = D / 16;  // contraction steps of QK^T
   constexpr int DB = D / 32;  // 32-channel blocks of the output
@@ -495,12 +496,13 @@ int launch_pass_bf16(const PassArgs& a, void* stream) {
       kpre, vtpre, a.vt_pre_tiles_per_head, a.part_rows, a.Hq, a.Hkv, a.group, a.scale)
 #define PA_LAUNCH_D(DD)                                                                                            \
   if (!a.causal) PA_LAUNCH(DD, false, 0, false);                                                                   \
+  else if (a.epilogue == 0 && a.sweep_prefix) PA_LAUNCH(DD, true, 0, true);                                        \
   else if (a.epilogue == 0) PA_LAUNCH(DD, true, 0, false);                                                         \
   else if (a.epilogue == 1 && a.sweep_prefix) PA_LAUNCH(DD, true, 1, true);                                        \
   else if (a.epilogue == 1) PA_LAUNCH(DD, true, 1, false);                                                         \
   else PA_LAUNCH(DD, true, 2, false)
   if (a.epilogue < 0 || a.epilogue > 2 || (!a.causal && a.epilogue != 0)) return 1;
-  if (a.sweep_prefix && (a.epilogue != 1 || !a.k_pre || !a.vt_pre)) return 1;
+  if (a.sweep_prefix && (!a.causal || a.epilogue == 2 || !a.k_pre || !a.vt_pre)) return 1;
   if (a.D == 128) {
     PA_LAUNCH_D(128);
   } else {

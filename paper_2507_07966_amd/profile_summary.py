@@ -26,7 +26,7 @@ def short_name(k: str) -> str:
         if not causal:
             return "prefix_pass (bf16 MFMA)"
         if sweep:
-            return "attention_sweep (bf16 MFMA)"
+            return "attention_sweep (bf16 MFMA)" + (", fp32 partial" if epi == 0 else "")
         return "suffix_pass (bf16 MFMA)" + ("" if epi == 0 else ", final" if epi == 1 else ", merging")
     if "bwd_dkv_reduce" in k:
         return "bwd_dkv: add partial gradients"

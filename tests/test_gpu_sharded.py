@@ -50,6 +50,9 @@ CASES = [
     ("bf16", 14, 2, 64, 513, (100, 300), [0, 1, 2, 257, 513], 3),           # tiny shards; suffix on the last shard
     ("bf16", 8, 1, 128, 0, (65, 64), [0, 0], 0),                            # no prefix at all
     ("bf16", 8, 2, 128, 3000, (20, 9), [0, 1500, 3000], 1),                 # few rows: each shard's keys are split again inside the call
+    # the shard with the own keys has more than 1,024 key tiles and enough rows to stay unsplit: prefix pass,
+    # suffix pass and the two-way merge into an fp32 partial instead of one sweep
+    ("bf16", 2, 2, 64, 66000, (9000, 7600), [0, 65800, 66000], 0),
     ("f32", 4, 2, 64, 100, (33, 70), [0, 30, 100], 1),
 ]
 

@@ -35,10 +35,14 @@ def run_static(x):
 
 @pytest.mark.gpu
 def test_static_workspace_forward_two_calls_second_smaller():
-    cases = [wl.make_custom("bf16", 2, 2, 64, 65600, (4000, 2500, 3756), seed=40),   # prefix pass + merging suffix pass
+    cases = [wl.make_custom("bf16", 2, 2, 64, 65600, (9000, 7600), seed=40),         # prefix pass + merging suffix pass
              wl.make_custom("bf16", 28, 4, 128, 700, (300, 129, 77), seed=41),       # smaller: one sweep
              wl.make_custom("bf16", 28, 4, 128, 5000, (40, 3), seed=42),             # prefix key ranges + n-way merge
              wl.make_custom("f32", 4, 2, 64, 100, (33, 70), seed=43)]                # fp32: stand-alone merge kernel
+    import paper_2507_07966_amd as pa
+    probe = pa.prefix_attn_plan(2, 2, 64, 65600, [9000, 7600], 64 ** -0.5, dtype="bf16", device=-1)
+    assert len(probe.items(3)) == 0 and len(set(probe.items(0)[:, 5].tolist())) == 1   # no sweep, one key range
+    probe.destroy()
     for x in cases:
         w = x.workload
         print(f"static workspace case {w.dtype} P={w.prefix_len} lens={x.suffix_lens.tolist()}", flush=True)
