@@ -66,6 +66,52 @@ def test_static_workspace_rejects_a_plan_that_does_not_fit():
     plan.destroy()
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("Hq,Hkv,D,P,lens", [(28, 4, 128, 700, (300, 129, 77)),     # one sweep
+                                              (28, 4, 128, 5000, (40, 3))])           # prefix key ranges + n-way merge
+def test_static_workspace_forward_replays_in_a_captured_graph(Hq, Hkv, D, P, lens):
+    """One of the callers the allocation-free entry point is for: a captured HIP graph.  The call is captured
+    once and replayed three times, each time on new inputs copied into the same buffers, with the program's own
+    eager work and synchronisations between the replays; every replay must equal, bit for bit, the eager call on
+    the same inputs."""
+    import torch
+    import paper_2507_07966_amd as pa
+    names = ("q", "k_prefix", "v_prefix", "k_suffix", "v_suffix")
+    x = wl.make_custom("bf16", Hq, Hkv, D, P, lens, seed=60)
+    dev = {n: to_device(x, n) for n in names}
+    plan = pa.prefix_attn_plan(Hq, Hkv, D, P, list(lens), x.workload.scale, dtype="bf16", device=0)
+    assert plan.workspace_bytes <= pa.STATIC_SCRATCH_BYTES
+    T = x.total_suffix
+    out = torch.zeros((T, Hq, D), device="cuda", dtype=torch.bfloat16)
+    lse = torch.zeros((Hq, T), device="cuda", dtype=torch.float32)
+
+    def call():
+        pa.prefix_attn_forward_static(plan, dev["q"], dev["k_prefix"], dev["v_prefix"], dev["k_suffix"],
+                                      dev["v_suffix"], out, lse)
+
+    call()                       # eager once: nothing is resolved or loaded for the first time under capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        call()
+    for seed in (61, 62, 63):
+        xn = wl.make_custom("bf16", Hq, Hkv, D, P, lens, seed=seed)
+        for n in names:
+            dev[n].copy_(to_device(xn, n))
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        out_g, lse_g = out.clone(), lse.clone()
+        out.fill_(float("nan"))
+        lse.fill_(float("nan"))
+        call()
+        torch.cuda.synchronize()
+        assert torch.isfinite(out_g.float()).all() and torch.isfinite(lse_g).all()
+        assert torch.equal(out_g, out) and torch.equal(lse_g, lse), f"replay with seed {seed} differs from the eager call"
+    plan.destroy()
+
+
 def test_static_workspace_argument_checks_need_no_gpu():
     """The size limit is checked first, then the plan's device: both before anything touches a GPU."""
     import paper_2507_07966_amd as pa
