@@ -4,7 +4,7 @@ import pytest
 
 from oracle import cref
 from paper_2507_07966_amd import workloads as wl
-from tests.gpu_util import check, check_grads, few_keys_floor, run_hip_backward
+from tests.gpu_util import check, check_grads, delta_error_sigma, run_hip_backward
 from tests.random_shapes import random_shapes
 
 pytestmark = pytest.mark.gpu
@@ -22,4 +22,4 @@ def test_random_shape_forward_and_backward(Hq, Hkv, D, P, lens):
     ro, rl, _ = cref.prefix_shared_attention(*a)
     check(out, lse, ro, rl, f"random {Hq}/{Hkv}/{D} P={P} {lens}")
     check_grads(got, cref.prefix_shared_attention_backward(*a, do)[:5], "bf16", f"random {Hq}/{Hkv}/{D} P={P} {lens}",
-                few_keys_floor(x, do))
+                sigmas=delta_error_sigma(x, do))
