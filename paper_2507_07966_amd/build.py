@@ -72,5 +72,23 @@ def build(verbose: bool = False, extra_flags=(), out: str = LIB) -> str:
     return out
 
 
+PROBE = os.path.join(HERE, "power_probe")
+
+
+def build_probe(out: str = PROBE) -> str:
+    """The stand-alone measurement program csrc/power_probe.hip (MFMA rate under the power limit, with and without
+    LDS operand reads): not part of the library, built beside it so that its record under profiles/ can be re-made."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", *DEVICE_FLAGS[:4], "-Wall",
+           "-Wno-unused-command-line-argument", os.path.join(CSRC, "power_probe.hip"), "-o", out]
+    r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    log = "\n".join(l for l in r.stdout.splitlines() if l.strip() != HOST_PASS_NOTE)
+    if r.returncode != 0:
+        print(f"[build] power_probe.hip FAILED\n{log}", file=sys.stderr)
+        raise RuntimeError("hipcc failed")
+    return out
+
+
 if __name__ == "__main__":
     print(build(verbose="-v" in sys.argv))
+    print(build_probe())

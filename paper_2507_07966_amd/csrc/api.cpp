@@ -85,6 +85,7 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
   a.group = plan->group;
   a.scale = d.softmax_scale;
   a.part_rows = plan->T * d.num_q_heads;
+  a.flags = reinterpret_cast<int32_t*>(ws + plan->off_flags);  // bf16 passes only
   // With key splits the prefix pass leaves `ks` partials in the workspace and an n-way merge
   // combines them (and the suffix partial) instead of the two-way merge.
   const int ks = plan->key_splits;
@@ -125,6 +126,7 @@ int enqueue_forward(const prefix_attn_plan_t* plan, const void* q, const void* k
     t.G = d.num_rollouts;
     t.Hkv = d.num_kv_heads;
     t.D = d.head_dim;
+    t.order_32x32 = false;  // the attention passes contract with 16 x 16 x 32 MFMAs
     if (pa::launch_vt_images(t, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;

@@ -88,6 +88,7 @@ int enqueue_backward(const prefix_attn_plan_t* plan, const BackwardArgs& x, void
     t.G = d.num_rollouts;
     t.Hkv = d.num_kv_heads;
     t.D = d.head_dim;
+    t.order_32x32 = true;  // the dQ pass contracts with 32 x 32 x 16 MFMAs
     if (pa::launch_vt_images(t, hip_stream) != 0) return PA_ERR_HIP;
   }
   if (ev && hipEventRecord(ev[1], hs) != hipSuccess) return PA_ERR_HIP;

@@ -13,6 +13,7 @@ namespace pa {
 // Tile geometry of the two attention passes: one work item = ROWS_PER_ITEM stacked query
 // rows of one (kv head, rollout); keys are swept in LDS tiles of KEYS_PER_TILE.
 constexpr int ROWS_PER_ITEM = 256;
+constexpr int WAVES_PER_ITEM = 8;   // wavefronts of the bf16 attention kernels' workgroup (32 rows each)
 constexpr int KEYS_PER_TILE = 64;
 // The layout the work lists are tuned for (MI355X): 256 compute units in 8 XCDs, workgroup n dispatched to
 // XCD n % 8.  A plan for a device that reports another compute-unit count (a partitioned GPU, say) uses that
@@ -88,6 +89,9 @@ struct PassArgs {
   const void* k_pre;           // [P, Hkv, D]
   const void* vt_pre;          // prefix V tile images
   int64_t vt_pre_tiles_per_head;
+  // bf16: one word per (work item, wavefront), written by the common kernel of a pass and read by its careful
+  // kernel (see attn_bf16.hip); [num_items][WAVES_PER_ITEM]
+  int32_t* flags;
 };
 
 struct MergeArgs {
@@ -116,6 +120,9 @@ struct VtArgs {
   const int32_t* vt_off;  // [G+1]
   int64_t P;
   int32_t tiles_prefix, tiles_suffix, G, Hkv, D;
+  // order of the 64 keys inside a row of an image: false = as the 16 x 16 x 32 MFMAs of the forward passes deliver
+  // a query's probabilities, true = as the 32 x 32 x 16 MFMAs of the backward's dQ pass deliver its dS
+  bool order_32x32;
 };
 int launch_vt_images(const VtArgs& a, void* stream);
 int launch_merge(const MergeArgs& a, void* stream);
@@ -160,7 +167,8 @@ struct prefix_attn_plan {
   std::vector<pa::WorkItem> sweep_items;
   pa::WorkItem* d_sweep_items = nullptr;
   // workspace layout, byte offsets
-  size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, ws_bytes = 0;
+  size_t off_o1 = 0, off_o2 = 0, off_lse1 = 0, off_lse2 = 0, off_lse = 0, off_vtp = 0, off_vts = 0, off_flags = 0,
+         ws_bytes = 0;
   // backward: dK/dV work lists (0 = prefix key blocks, 1 = suffix key blocks) and workspace layout
   std::vector<pa::KeyItem> key_items[2];
   pa::KeyItem* d_key_items[2] = {nullptr, nullptr};

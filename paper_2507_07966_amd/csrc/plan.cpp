@@ -362,6 +362,11 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
     const size_t image = (size_t)desc->head_dim * pa::KEYS_PER_TILE * 2;
     p->off_vts = p->off_vtp + align_up((size_t)desc->num_kv_heads * p->tiles_prefix * image, 256);
     end = p->off_vts + align_up((size_t)desc->num_kv_heads * p->tiles_suffix * image, 256);
+    // one word per (work item, wavefront) of the longest work list: a pass's common kernel tells its careful
+    // kernel which items to redo; the passes run one after the other and share the region
+    const size_t items = std::max({p->items[0].size(), p->items[1].size(), p->sweep_items.size()});
+    p->off_flags = end;
+    end += align_up(items * pa::WAVES_PER_ITEM * sizeof(int32_t), 256);
   }
   p->ws_bytes = end;
   layout_backward_workspace(*p);

@@ -4,9 +4,14 @@
 // direct-to-LDS loads and read MFMA A-operands of V^T with conflict-free 16-byte LDS reads.
 //
 // Image layout (D rows of 128 bytes; row d holds the 64 keys of the tile for channel d):
-//   - key k of the tile sits in slot s = 16*(k/16) + swap_bits_2_3(k%16): inside every group
-//     of 16 keys the order is 0-3, 8-11, 4-7, 12-15.  That is the order in which the score
-//     accumulator of S^T = K Q^T hands the probabilities of one query to the lane halves.
+//   - forward passes (v_mfma_f32_16x16x32_bf16): inside every group of 32 keys, slot 8*g + e (g = 0..3,
+//     e = 0..7) holds key 4*g + e (e < 4) or 16 + 4*g + (e - 4): keys 0-3, 16-19, 4-7, 20-23, 8-11, 24-27,
+//     12-15, 28-31.  That is the order in which two 16 x 16 score accumulator blocks of S^T = K Q^T hand the
+//     probabilities of one query to the four lanes that share it (lane group g contracts over slots
+//     8*g .. 8*g + 7).
+//   - the backward's dQ pass (v_mfma_f32_32x32x16_bf16, images of K): key k of the tile sits in slot
+//     16*(k/16) + swap_bits_2_3(k%16), i.e. inside every group of 16 keys the order is 0-3, 8-11, 4-7, 12-15, the
+//     order in which a 32 x 32 accumulator block hands its values to the two lane halves.
 //   - the 16-byte chunk j = s/8 of row d is stored at chunk position j ^ ((d >> 1) & 7), which
 //     spreads the rows a wavefront reads together over all LDS banks.
 //   - keys past the end of the sequence are zero.
@@ -24,7 +29,7 @@ namespace {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
 
-template <int D>
+template <int D, bool ORDER32>
 __global__ __launch_bounds__(256) void vt_image_kernel(const unsigned short* __restrict__ v_prefix,
                                                        const unsigned short* __restrict__ v_suffix,
                                                        unsigned short* __restrict__ vt_prefix,
@@ -77,9 +82,15 @@ __global__ __launch_bounds__(256) void vt_image_kernel(const unsigned short* __r
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const int s = j * 8 + e;                    // slot
-      const int lo = s & 15;
-      const int kin = (lo & 3) | ((lo & 4) << 1) | ((lo & 8) >> 1);  // swap bits 2 and 3
-      w[e] = t[((s & ~15) + kin) * LD + d];
+      int key;
+      if (ORDER32) {
+        const int lo = s & 15;
+        key = (s & ~15) + ((lo & 3) | ((lo & 4) << 1) | ((lo & 8) >> 1));  // swap bits 2 and 3
+      } else {
+        const int g = (s >> 3) & 3;               // lane group inside the 32-key chunk
+        key = (s & ~31) + (e < 4 ? 4 * g + e : 16 + 4 * g + (e - 4));
+      }
+      w[e] = t[key * LD + d];
     }
     *reinterpret_cast<u16x8*>(dst + (int64_t)n * 8) = w;
   }
@@ -95,12 +106,15 @@ int launch_vt_images(const VtArgs& a, void* stream) {
   auto vs = static_cast<const unsigned short*>(a.v_suffix);
   auto tp = static_cast<unsigned short*>(a.vt_prefix);
   auto ts = static_cast<unsigned short*>(a.vt_suffix);
-  if (a.D == 128)
-    vt_image_kernel<128><<<(unsigned)blocks, 256, 0, s>>>(vp, vs, tp, ts, a.cu, a.vt_off, a.P, a.tiles_prefix,
-                                                            a.tiles_suffix, a.G, a.Hkv);
-  else
-    vt_image_kernel<64><<<(unsigned)blocks, 256, 0, s>>>(vp, vs, tp, ts, a.cu, a.vt_off, a.P, a.tiles_prefix,
-                                                           a.tiles_suffix, a.G, a.Hkv);
+#define PA_VT(DD, OO)                                                                                            \
+  vt_image_kernel<DD, OO><<<(unsigned)blocks, 256, 0, s>>>(vp, vs, tp, ts, a.cu, a.vt_off, a.P, a.tiles_prefix, \
+                                                            a.tiles_suffix, a.G, a.Hkv)
+  if (a.D == 128) {
+    if (a.order_32x32) PA_VT(128, true); else PA_VT(128, false);
+  } else {
+    if (a.order_32x32) PA_VT(64, true); else PA_VT(64, false);
+  }
+#undef PA_VT
   return (int)hipGetLastError();
 }
 
