@@ -9,11 +9,13 @@
 //
 // Kernel 1 (bf16 MFMA GEMM with a reducing epilogue).  A workgroup (8 wavefronts) computes one
 // 256-vocabulary x 256-token tile of Z^T = W H^T: wavefront (wv, wt) owns 64 vocabulary rows x 128
-// tokens (2 x 4 accumulator blocks of v_mfma_f32_32x32x16_bf16, 128 registers).  W and H panels of
+// tokens (4 x 8 accumulator blocks of v_mfma_f32_16x16x32_bf16, 128 registers; that shape moves half
+// the accumulator data per FLOP of the 32 x 32 x 16 one and sustains about 10 % more under the board's
+// power limit).  W and H panels of
 // 64 channels go global -> LDS through range-checked buffer loads (rows past the end of either
-// matrix read as zero), double buffered, one barrier per 64 channels; 6 LDS operand reads feed 8
-// MFMAs.  In the epilogue every lane holds 32 logits of each of 4 tokens: it reduces them to a
-// maximum and a sum of exponentials, combines with the lane holding the other 32 rows and, through
+// matrix read as zero), double buffered, one barrier per 64 channels; 12 LDS operand reads feed 32
+// MFMAs.  In the epilogue every lane holds 16 logits of each of 8 tokens: it reduces them to a
+// maximum and a sum of exponentials, combines with the three lanes holding the token's other rows and, through
 // LDS, with the other three row blocks, so the tile writes one (m, l) pair per token; the lane that
 // holds the target's logit writes it out.  Workgroups are numbered so that the 32 tiles running together on one XCD form an
 // 8-token-tile x 4-vocabulary-tile block: 12 distinct panels per step share that XCD's L2
@@ -37,13 +39,26 @@ constexpr int LP_STAGE = 2 * PANEL_BYTES;      // W panel, H panel
 constexpr float LOG2E = 1.4426950408889634f;
 constexpr float LN2 = 0.6931471805599453f;
 
-// Lane l and lane l ^ 32 hold the two halves of a token's column: both values, via
-// v_permlane32_swap (results read through named temporaries, see attn_bf16.hip).
+// v_mfma_f32_16x16x32_bf16 (l16 = lane % 16, g4 = lane / 16): A: lane holds row l16, contraction indices
+// 8*g4 .. 8*g4+7; B: column l16, the same indices; C: register i holds row 4*g4 + i, column l16.
+// The four lanes l16, l16 + 16, l16 + 32, l16 + 48 hold the 16 rows of a column: maximum / sum over them.
 __device__ inline void pair_values(float x, float& a, float& b) {
   auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  const unsigned r0 = r[0], r1 = r[1];
+  const unsigned r0 = r[0], r1 = r[1];   // read through named temporaries, see attn_bf16.hip
   a = __uint_as_float(r0);
   b = __uint_as_float(r1);
+}
+__device__ inline float column_max(float x) {
+  x = fmaxf(x, __shfl_xor(x, 16));
+  float u, w;
+  pair_values(x, u, w);
+  return fmaxf(u, w);
+}
+__device__ inline float column_sum(float x) {
+  x += __shfl_xor(x, 16);
+  float u, w;
+  pair_values(x, u, w);
+  return u + w;
 }
 
 __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
@@ -73,7 +88,7 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
   }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int l32 = lane & 31, hf = lane >> 5;
+  const int l16 = lane & 15, g4 = lane >> 4;
   const int wv = wave & 3, wt = wave >> 2;
   const int64_t v0 = (int64_t)tv * LP_TILE, t0 = (int64_t)tm * LP_TILE;
 
@@ -100,25 +115,25 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
     }
   };
 
-  f32x16 C[2][4];
+  constexpr int NA = 4, NB = 8;   // 16-row blocks of the wavefront's 64 vocabulary rows / 128 tokens
+  f32x4 C[NA][NB];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < NA; ++a)
 #pragma unroll
-    for (int b = 0; b < 4; ++b)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) C[a][b][i] = 0.f;
+    for (int b = 0; b < NB; ++b) C[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
   // Per-lane LDS addresses of the operand reads, one set per buffer (the second buffer lies 64 KiB on,
   // beyond the reach of a read's immediate offset), so the main loop itself holds no address arithmetic.
-  const unsigned char* wop[2][BK / 16];
-  const unsigned char* hop[2][BK / 16];
+  // (Row blocks of 16 share the swizzle of rows 0..15.)
+  const unsigned char* wop[2][BK / 32];
+  const unsigned char* hop[2][BK / 32];
 #pragma unroll
   for (int bufi = 0; bufi < 2; ++bufi)
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      const int off = row_operand_offset<BK>(l32, hf, kk);
-      wop[bufi][kk] = smem + bufi * LP_STAGE + (wv * 64) * 128 + off;
-      hop[bufi][kk] = smem + bufi * LP_STAGE + PANEL_BYTES + (wt * 128) * 128 + off;
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      const int off = l16 * 128 + (((4 * ks + g4) ^ swizzle_term(l16, 128)) << 4);
+      wop[bufi][ks] = smem + bufi * LP_STAGE + (wv * 64) * 128 + off;
+      hop[bufi][ks] = smem + bufi * LP_STAGE + PANEL_BYTES + (wt * 128) * 128 + off;
     }
 
   const int nstages = (d + BK - 1) / BK;  // channels past d read as zero (range-checked loads)
@@ -132,16 +147,16 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
     // the one still issuing loads (+1.5 %; priority for the loads instead: -0.4 %).
     __builtin_amdgcn_s_setprio(1);
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 wa[2], hb[4];
+    for (int ks = 0; ks < BK / 32; ++ks) {
+      bf16x8 wa[NA], hb[NB];
 #pragma unroll
-      for (int a = 0; a < 2; ++a) wa[a] = lds_operand(wop[BUF][kk] + a * 32 * 128);
+      for (int a = 0; a < NA; ++a) wa[a] = lds_operand(wop[BUF][ks] + a * 16 * 128);
 #pragma unroll
-      for (int b = 0; b < 4; ++b) hb[b] = lds_operand(hop[BUF][kk] + b * 32 * 128);
+      for (int b = 0; b < NB; ++b) hb[b] = lds_operand(hop[BUF][ks] + b * 16 * 128);
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) C[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wa[a], hb[b], C[a][b], 0, 0, 0);
+        for (int a = 0; a < NA; ++a) C[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wa[a], hb[b], C[a][b], 0, 0, 0);
     }
     __builtin_amdgcn_s_setprio(0);
   };
@@ -155,53 +170,42 @@ __global__ __launch_bounds__(LP_THREADS, 1) void logprob_tile_kernel(
     if (s < nstages) stage(s, std::integral_constant<int, 0>{});
   }
 
-  // ---- epilogue.  Register i of C[a][b]: vocabulary row v0 + wv*64 + a*32 + 8*(i/4) + 4*hf + i%4,
-  //      token t0 + wt*128 + b*32 + l32.
+  // ---- epilogue.  Register i of C[a][b]: vocabulary row v0 + wv*64 + a*16 + 4*g4 + i,
+  //      token t0 + wt*128 + b*16 + l16.
   const float c2 = logit_scale * LOG2E;  // work in base 2
   __syncthreads();                        // every wavefront is done with the panels: reuse the LDS
   float2* stage_ml = reinterpret_cast<float2*>(smem);  // [4 row blocks][256 tokens] (m in base-2 units, l)
+  const int64_t vlane = v0 + wv * 64 + 4 * g4;         // this lane's first vocabulary row
 #pragma unroll
-  for (int b = 0; b < 4; ++b) {
-    const int64_t tok = t0 + wt * 128 + b * 32 + l32;
+  for (int b = 0; b < NB; ++b) {
+    const int64_t tok = t0 + wt * 128 + b * 16 + l16;
     float m = -INFINITY;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int64_t vrow = v0 + wv * 64 + a * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
-        if (vrow < V) m = fmaxf(m, C[a][b][i]);
-      }
-    {
-      float u, w2;
-      pair_values(m, u, w2);
-      m = fmaxf(u, w2) * c2;  // -inf only when none of the block's 64 rows exists
-    }
+      for (int i = 0; i < 4; ++i)
+        if (vlane + a * 16 + i < V) m = fmaxf(m, C[a][b][i]);
+    m = column_max(m) * c2;  // -inf only when none of the block's 64 rows exists
     float l = 0.f;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const int64_t vrow = v0 + wv * 64 + a * 32 + 8 * (i / 4) + 4 * hf + (i % 4);
-        if (vrow < V) l += __builtin_amdgcn_exp2f(__builtin_fmaf(C[a][b][i], c2, -m));
-      }
-    {
-      float u, w2;
-      pair_values(l, u, w2);
-      l = u + w2;
-    }
-    if (hf == 0) stage_ml[wv * LP_TILE + wt * 128 + b * 32 + l32] = float2{m, l};  // m = -inf, l = 0 for a block past V
+      for (int i = 0; i < 4; ++i)
+        if (vlane + a * 16 + i < V) l += __builtin_amdgcn_exp2f(__builtin_fmaf(C[a][b][i], c2, -m));
+    l = column_sum(l);
+    if (g4 == 0) stage_ml[wv * LP_TILE + wt * 128 + b * 16 + l16] = float2{m, l};  // m = -inf, l = 0 for a block past V
     if (tok < N) {
-      // the target's logit, if it lies in this wavefront's 64 rows and this lane's half
+      // the target's logit, if it lies in this wavefront's 64 rows and this lane's four of every 16
       const int64_t rel = (int64_t)targets[tok] - (v0 + wv * 64);
       if (rel >= 0 && rel < 64) {
-        const int r = (int)rel & 31, a_t = (int)rel >> 5;
-        if (((r >> 2) & 1) == hf) {
-          const int i_t = 4 * (r >> 3) + (r & 3);
+        const int r = (int)rel & 15, a_t = (int)rel >> 4;
+        if ((r >> 2) == g4) {
+          const int i_t = r & 3;
           float z = 0.f;
 #pragma unroll
-          for (int a = 0; a < 2; ++a)
+          for (int a = 0; a < NA; ++a)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
+            for (int i = 0; i < 4; ++i)
               if (a == a_t && i == i_t) z = C[a][b][i];
           target_logit[tok] = z * logit_scale;
         }

@@ -17,12 +17,14 @@ import sys
 
 
 def short_name(k: str) -> str:
-    # mangled template arguments: <head_dim, causal, epilogue, sweep> / <head_dim, causal, partial> / <head_dim, partial>
+    # mangled template arguments: <head_dim, causal, epilogue, sweep, careful> / <head_dim, causal, partial> / <head_dim, partial>
     if "pass_bf16_kernel" in k:
-        m = re.search(r"pass_bf16_kernelILi\d+ELb(\d)ELi(\d)ELb(\d)E", k)
+        m = re.search(r"pass_bf16_kernelILi\d+ELb(\d)ELi(\d)ELb(\d)ELb(\d)E", k)
         if m is None:
             return "attention pass (bf16 MFMA)"
-        causal, epi, sweep = (int(v) for v in m.groups())
+        causal, epi, sweep, careful = (int(v) for v in m.groups())
+        if careful:     # second launch of every pass: redoes the items the common kernel gave up on (none, normally)
+            return "careful kernel of the " + ("prefix pass" if not causal else "sweep" if sweep else "suffix pass")
         if not causal:
             return "prefix_pass (bf16 MFMA)"
         if sweep:
