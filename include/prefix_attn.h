@@ -90,6 +90,7 @@ int prefix_attn_plan(const prefix_attn_desc_t* desc, prefix_attn_plan_t** plan_o
  *   out       [T, Hq,  D]  attention output, same dtype as q
  *   workspace              scratch of at least the planned size; holds the two fp32
  *                          partial results, the merged LSE and (bf16) the V tile images
+ *                          and the per-work-item flags the two kernels of a pass share
  * Argument errors are reported before anything is launched. */
 int prefix_attn_forward(const prefix_attn_plan_t* plan, const void* q, const void* k_prefix,
                         const void* v_prefix, const void* k_suffix, const void* v_suffix, void* out,

@@ -57,8 +57,9 @@ def short_name(k: str) -> str:
         return "merge_partials (n-way)"
     if "merge_kernel" in k:
         return "merge"
-    if "vt_image_kernel" in k:
-        return "v_layout_prepass"
+    if "vt_image_kernel" in k:      # <head_dim, key order of the 32x32x16 products>: the backward's images of K
+        # (rocprofv3 prints short names demangled, long ones mangled)
+        return "k_layout_prepass (backward)" if re.search(r"vt_image_kernel(ILi\d+ELb1E|<\d+, true>)", k) else "v_layout_prepass"
     if "lse_export" in k:
         return "lse_export"
     if "elementwise" in k and "Mul" in k or "mul" in k.lower() and "elementwise" in k:
